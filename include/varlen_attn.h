@@ -1,0 +1,137 @@
+/*
+ * varlen_attn.h -- C ABI of the packed variable-length causal attention library
+ * for AMD MI355X (gfx950).
+ *
+ * The operation: a padding-free packed token stream [R rows, T tokens per row]
+ * carries position ids that run 0..L-1 inside each example and restart at 0
+ * (paper, Section 3 and Section 3.1).  The restart marks the example boundary.
+ * From the ids the library derives cu_seqlens (Section 3, last paragraph) and
+ * runs causal softmax attention, forward and backward, in which a token
+ * attends only to earlier tokens of its own example ("correct cross-attention",
+ * Table 1).  Rows are separate batch elements: token 0 of a row always starts
+ * an example.
+ *
+ * Conventions
+ *   - Unless marked "host", every pointer is DEVICE memory owned by the caller.
+ *     The library allocates nothing, frees nothing and never synchronises; all
+ *     work is enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).
+ *   - Arguments are validated on the host before anything is launched; a
+ *     non-zero status means nothing was enqueued (VA_ERR_HIP excepted).
+ *   - Tensors are contiguous, token-major:
+ *         Q, O, dO, dQ : [N, Hq,  d]      N = R * T
+ *         K, V, dK, dV : [N, Hkv, d]
+ *         LSE          : [Hq, N] float
+ *     Query head h reads KV head h / (Hq / Hkv); Hq % Hkv == 0 is required.
+ *   - Outputs are fully overwritten; inputs are never modified.
+ *   - One va_pack_to_cu_seqlens call serves any number of forward / backward
+ *     calls on the same packed stream (every layer of a model shares it).
+ */
+#ifndef VARLEN_ATTN_H
+#define VARLEN_ATTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  VA_OK = 0,
+  VA_ERR_NULL = 1,        /* a required pointer is NULL                                    */
+  VA_ERR_SHAPE = 2,       /* rows/tokens/heads/head_dim <= 0, N >= 2^31, Hq % Hkv != 0      */
+  VA_ERR_UNSUPPORTED = 3, /* unknown dtype / id type, head_dim > 256                        */
+  VA_ERR_WORKSPACE = 4,   /* plan buffer or workspace smaller than the *_bytes() query says */
+  VA_ERR_HIP = 5          /* a launch failed (hipGetLastError after the launch)             */
+} va_status;
+
+typedef enum { VA_F32 = 0, VA_BF16 = 1 } va_dtype;  /* element type of Q/K/V/O/dO and of the gradients */
+typedef enum { VA_I32 = 0, VA_I64 = 1 } va_itype;   /* element type of position_ids                     */
+
+/* Rows of Q (forward, dQ) or of K/V (dK/dV) handled by one workgroup; the
+ * schedule below is expressed in tiles of this many consecutive tokens of a row. */
+#define VA_TILE 128
+
+/*
+ * Example boundaries and tile schedule of one packed stream.  A host struct of
+ * device pointers into the caller's plan buffer; filled by va_segments_bind,
+ * whose contents are written by va_pack_to_cu_seqlens.
+ */
+typedef struct va_segments {
+  int32_t *cu_seqlens;    /* [N+1] capacity; entries 0..n valid: start token of each example, cu[n] = N */
+  int32_t *seg_id;        /* [N]  index of the example holding token t                                   */
+  int32_t *seg_start;     /* [N]  first token of that example  (= cu[seg_id[t]])                         */
+  int32_t *seg_end;       /* [N]  one past its last token      (= cu[seg_id[t] + 1])                     */
+  int32_t *meta;          /* [8]  meta[0] = n (examples), meta[1] = max_seqlen; rest reserved            */
+  int32_t *q_tile_order;  /* [R * ceil(T / VA_TILE)] query tiles, most key tiles first                   */
+  int32_t *kv_tile_order; /* [R * ceil(T / VA_TILE)] key tiles, most query rows first                    */
+  int32_t *scratch;       /* internal: per-chunk partial scans and tile costs                            */
+} va_segments;
+
+/* Bytes of device memory a plan buffer for a [rows, tokens_per_row] stream needs (0 on bad shape). */
+size_t va_plan_bytes(int32_t rows, int32_t tokens_per_row);
+
+/* Carve `plan` (device, >= va_plan_bytes, 256-byte aligned) into the arrays of `seg` (host struct).
+ * Host-only pointer arithmetic; launches nothing. */
+va_status va_segments_bind(void *plan, size_t plan_bytes, int32_t rows, int32_t tokens_per_row,
+                           va_segments *seg /* host, out */);
+
+/*
+ * position_ids -> cu_seqlens (paper, Section 3: "compute cu_seq_len from position_ids").
+ *   position_ids : device, [rows, tokens_per_row] of `it`.  Token t starts an example iff it is
+ *                  the first token of its row or its id equals 0; other values are not inspected.
+ *   seg          : host struct bound to a plan buffer; all its arrays are written, including
+ *                  the tile schedule (which query/key tiles exist and in which order to run them).
+ * Integer work only; results are exact.
+ */
+va_status va_pack_to_cu_seqlens(const void *position_ids, va_itype it, int32_t rows,
+                                int32_t tokens_per_row, const va_segments *seg, void *stream);
+
+/* Workspace bytes for one forward (is_bwd = 0) or backward (is_bwd = 1) call (0 on bad shape). */
+size_t va_attn_workspace_bytes(int32_t n_tokens, int32_t hq, int32_t hkv, int32_t d, int is_bwd);
+
+/*
+ * Forward: for every example [a, b), head h, token i in [a, b):
+ *     S_ij = softmax_scale * q_i . k_j  (a <= j <= i),  P_i = softmax_j(S_i),
+ *     O_i = sum_j P_ij v_j,  LSE[h, i] = log sum_j exp(S_ij)   (natural log)
+ * (the varlen attention routine the paper's Section 3 hands cu_seqlens to; the mask is
+ * Table 1's "correct cross-attention").  Only key tiles that intersect an example's
+ * causal triangle are visited.
+ *   dt            : element type of Q, K, V, O.  VA_BF16 with d == 128 runs the MFMA kernels;
+ *                   other (dt, d <= 256) combinations run a plain fp32-arithmetic kernel.
+ *   softmax_scale : <= 0 means 1 / sqrt(d).
+ *   workspace     : >= va_attn_workspace_bytes(..., 0) bytes (may be NULL when that is 0).
+ */
+va_status va_varlen_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                             const va_segments *seg, int32_t rows, int32_t tokens_per_row,
+                             int32_t hq, int32_t hkv, int32_t d, va_dtype dt, float softmax_scale,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Backward of the above for loss = sum(O * dO), from the saved O and LSE:
+ *     P_ij = exp(S_ij - LSE_i),  dP_ij = dO_i . v_j,  D_i = dO_i . O_i,  dS_ij = P_ij (dP_ij - D_i)
+ *     dQ_i = scale * sum_j dS_ij k_j
+ *     dK_j = scale * sum_{i >= j} dS_ij q_i,   dV_j = sum_{i >= j} P_ij dO_i
+ * with dK, dV also summed over the Hq / Hkv query heads of a KV head.  Same mask, same
+ * skipped tiles.  Results are deterministic (no atomics).
+ *   grad_dt   : element type of dQ, dK, dV (VA_F32 or VA_BF16), independent of dt.
+ *   workspace : >= va_attn_workspace_bytes(..., 1) bytes (holds D, [Hq, N] float).
+ */
+va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const void *V,
+                             const void *O, const float *LSE, void *dQ, void *dK, void *dV,
+                             va_dtype grad_dt, const va_segments *seg, int32_t rows,
+                             int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
+                             va_dtype dt, float softmax_scale, void *workspace,
+                             size_t workspace_bytes, void *stream);
+
+/* Static string for a status code. */
+const char *va_status_string(va_status s);
+
+/* Library version string (host). */
+const char *va_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VARLEN_ATTN_H */

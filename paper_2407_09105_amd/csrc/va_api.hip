@@ -1,0 +1,164 @@
+// C ABI of the library: argument validation and dispatch.  See include/varlen_attn.h.
+#include <cstdlib>
+#include <cstring>
+
+#include "va_internal.h"
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+struct PlanLayout {
+  size_t cu, seg_id, seg_start, seg_end, meta, q_order, kv_order, scratch, total;
+};
+
+bool plan_layout(int32_t rows, int32_t T, PlanLayout *L) {
+  if (rows <= 0 || T <= 0) return false;
+  const long long N = (long long)rows * T;
+  if (N >= (1ll << 31) - 1) return false;
+  const size_t n = (size_t)N;
+  const size_t ntiles = (size_t)rows * (size_t)va::ceil_div(T, va::kTile);
+  const size_t nchunks = (n + va::kScanChunk - 1) / va::kScanChunk;
+  size_t off = 0;
+  L->cu = off;        off += align_up((n + 1) * 4);
+  L->seg_id = off;    off += align_up(n * 4);
+  L->seg_start = off; off += align_up(n * 4);
+  L->seg_end = off;   off += align_up(n * 4);
+  L->meta = off;      off += align_up(8 * 4);
+  L->q_order = off;   off += align_up(ntiles * 4);
+  L->kv_order = off;  off += align_up(ntiles * 4);
+  L->scratch = off;   off += align_up((6 * nchunks + 2 * ntiles) * 4);
+  L->total = off;
+  return true;
+}
+
+bool use_mfma(va_dtype dt, int d) {
+  static const bool force_generic = [] {
+    const char *e = std::getenv("VA_FORCE_GENERIC");
+    return e && e[0] == '1';
+  }();
+  return dt == VA_BF16 && d == 128 && !force_generic;
+}
+
+va_status check_common(const va_segments *seg, int32_t rows, int32_t T, int32_t hq, int32_t hkv,
+                       int32_t d, va_dtype dt) {
+  if (!seg) return VA_ERR_NULL;
+  if (!seg->cu_seqlens || !seg->seg_id || !seg->seg_start || !seg->seg_end || !seg->meta ||
+      !seg->q_tile_order || !seg->kv_tile_order)
+    return VA_ERR_NULL;
+  if (rows <= 0 || T <= 0 || hq <= 0 || hkv <= 0 || d <= 0) return VA_ERR_SHAPE;
+  if ((long long)rows * T >= (1ll << 31) - 1) return VA_ERR_SHAPE;
+  if (hq % hkv != 0) return VA_ERR_SHAPE;
+  if (dt != VA_F32 && dt != VA_BF16) return VA_ERR_UNSUPPORTED;
+  if (d > 256) return VA_ERR_UNSUPPORTED;
+  return VA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t va_plan_bytes(int32_t rows, int32_t tokens_per_row) {
+  PlanLayout L;
+  return plan_layout(rows, tokens_per_row, &L) ? L.total : 0;
+}
+
+va_status va_segments_bind(void *plan, size_t plan_bytes, int32_t rows, int32_t tokens_per_row,
+                           va_segments *seg) {
+  if (!plan || !seg) return VA_ERR_NULL;
+  PlanLayout L;
+  if (!plan_layout(rows, tokens_per_row, &L)) return VA_ERR_SHAPE;
+  if (plan_bytes < L.total || ((uintptr_t)plan % kAlign) != 0) return VA_ERR_WORKSPACE;
+  char *p = (char *)plan;
+  seg->cu_seqlens = (int32_t *)(p + L.cu);
+  seg->seg_id = (int32_t *)(p + L.seg_id);
+  seg->seg_start = (int32_t *)(p + L.seg_start);
+  seg->seg_end = (int32_t *)(p + L.seg_end);
+  seg->meta = (int32_t *)(p + L.meta);
+  seg->q_tile_order = (int32_t *)(p + L.q_order);
+  seg->kv_tile_order = (int32_t *)(p + L.kv_order);
+  seg->scratch = (int32_t *)(p + L.scratch);
+  return VA_OK;
+}
+
+va_status va_pack_to_cu_seqlens(const void *position_ids, va_itype it, int32_t rows,
+                                int32_t tokens_per_row, const va_segments *seg, void *stream) {
+  if (!position_ids || !seg) return VA_ERR_NULL;
+  if (!seg->cu_seqlens || !seg->seg_id || !seg->seg_start || !seg->seg_end || !seg->meta ||
+      !seg->q_tile_order || !seg->kv_tile_order || !seg->scratch)
+    return VA_ERR_NULL;
+  if (rows <= 0 || tokens_per_row <= 0) return VA_ERR_SHAPE;
+  if ((long long)rows * tokens_per_row >= (1ll << 31) - 1) return VA_ERR_SHAPE;
+  if (it != VA_I32 && it != VA_I64) return VA_ERR_UNSUPPORTED;
+  hipError_t e = va::launch_pack(position_ids, it, rows, tokens_per_row, *seg, (hipStream_t)stream);
+  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
+}
+
+size_t va_attn_workspace_bytes(int32_t n_tokens, int32_t hq, int32_t hkv, int32_t d, int is_bwd) {
+  if (n_tokens <= 0 || hq <= 0 || hkv <= 0 || d <= 0) return 0;
+  if (!is_bwd) return 0;
+  return align_up((size_t)n_tokens * (size_t)hq * sizeof(float));  // D = rowsum(dO * O), [Hq, N]
+}
+
+va_status va_varlen_attn_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
+                             const va_segments *seg, int32_t rows, int32_t tokens_per_row,
+                             int32_t hq, int32_t hkv, int32_t d, va_dtype dt, float softmax_scale,
+                             void *workspace, size_t workspace_bytes, void *stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  if (!Q || !K || !V || !O || !LSE) return VA_ERR_NULL;
+  va_status s = check_common(seg, rows, tokens_per_row, hq, hkv, d, dt);
+  if (s != VA_OK) return s;
+  const int N = rows * tokens_per_row;
+  const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
+  hipError_t e;
+  if (use_mfma(dt, d))
+    e = va::launch_mfma_fwd(Q, K, V, O, LSE, *seg, rows, tokens_per_row, hq, hkv, scale, (hipStream_t)stream);
+  else
+    e = va::launch_generic_fwd(Q, K, V, O, LSE, *seg, N, hq, hkv, d, dt, scale, (hipStream_t)stream);
+  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
+}
+
+va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const void *V,
+                             const void *O, const float *LSE, void *dQ, void *dK, void *dV,
+                             va_dtype grad_dt, const va_segments *seg, int32_t rows,
+                             int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
+                             va_dtype dt, float softmax_scale, void *workspace,
+                             size_t workspace_bytes, void *stream) {
+  if (!dO || !Q || !K || !V || !O || !LSE || !dQ || !dK || !dV) return VA_ERR_NULL;
+  va_status s = check_common(seg, rows, tokens_per_row, hq, hkv, d, dt);
+  if (s != VA_OK) return s;
+  if (grad_dt != VA_F32 && grad_dt != VA_BF16) return VA_ERR_UNSUPPORTED;
+  const int N = rows * tokens_per_row;
+  const size_t need = va_attn_workspace_bytes(N, hq, hkv, d, 1);
+  if (!workspace) return VA_ERR_NULL;
+  if (workspace_bytes < need) return VA_ERR_WORKSPACE;
+  const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
+  float *delta = (float *)workspace;
+  hipStream_t st = (hipStream_t)stream;
+  hipError_t e = va::launch_delta(dO, O, delta, N, hq, d, dt, st);
+  if (e != hipSuccess) return VA_ERR_HIP;
+  if (use_mfma(dt, d))
+    e = va::launch_mfma_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, rows, tokens_per_row, hq,
+                            hkv, scale, st);
+  else
+    e = va::launch_generic_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, N, hq, hkv, d, dt, scale, st);
+  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
+}
+
+const char *va_status_string(va_status s) {
+  switch (s) {
+    case VA_OK: return "ok";
+    case VA_ERR_NULL: return "null pointer";
+    case VA_ERR_SHAPE: return "bad shape";
+    case VA_ERR_UNSUPPORTED: return "unsupported dtype or head_dim";
+    case VA_ERR_WORKSPACE: return "plan buffer or workspace too small or misaligned";
+    case VA_ERR_HIP: return "HIP launch error";
+  }
+  return "unknown status";
+}
+
+const char *va_version(void) { return "varlen_attn 0.1 (gfx950)"; }
+
+}  // extern "C"

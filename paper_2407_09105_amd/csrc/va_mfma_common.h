@@ -1,0 +1,153 @@
+// Shared device helpers of the bf16 MFMA kernels (head_dim 128, gfx950).
+//
+// Matrix-core tile used throughout: v_mfma_f32_32x32x16_bf16, D[32x32] += A[32x16] * B[16x32].
+// Register layout per 64-lane wave (lane l, half = l / 32):
+//   A : lane holds row  l % 32, k = 8 * half .. 8 * half + 7   (8 bf16, contiguous in k)
+//   B : lane holds col  l % 32, k = 8 * half .. 8 * half + 7
+//   D : lane holds col  l % 32, 16 floats v = 0..15 at row 8 * (v / 4) + 4 * half + v % 4
+// All kernels keep the workgroup-resident index (query row in the forward and dQ kernels,
+// key row in the dK/dV kernel) on the lane/column axis, so that per-row softmax statistics
+// are per-lane scalars and the streamed index sits on the register axis, where it can feed
+// the next contraction as a B operand without leaving registers.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace va {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+constexpr int kD = 128;  // head_dim of the MFMA kernels
+
+__device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
+
+// Row (register axis) index of accumulator element v for a lane of the given half.
+__device__ __forceinline__ int acc_row(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
+
+// Eight consecutive accumulator floats v0..v0+7 -> one B operand (8 bf16).  With the layout
+// above these are rows {8a + 4 half + b : a in {2s2, 2s2+1}, b in 0..3} of a 16-row k-step.
+__device__ __forceinline__ bf16x8 pack_bf16x8(const f32x16 &x, int v0) {
+  bf16x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (__bf16)x[v0 + e];
+  return r;
+}
+
+// Position of streamed row j (0..63 within a 64-row block) inside a transposed LDS row, chosen
+// so that the 8 rows one lane needs for a k-step are contiguous: swap bits 2 and 3 of j.
+__device__ __forceinline__ int tr_pos(int j) { return (j & ~12) | ((j & 8) >> 1) | ((j & 4) << 1); }
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  bf16x2 r;
+  r.x = (__bf16)lo;
+  r.y = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+// 16-byte global load with a validity guard (zero when !ok)
+__device__ __forceinline__ u32x4 ldg16(const uint16_t *p, bool ok) {
+  u32x4 z = {0u, 0u, 0u, 0u};
+  return ok ? *(const u32x4 *)p : z;
+}
+
+// Cooperative copy of a [64 x 128] bf16 block of a [N, H, 128] tensor into LDS, row-major with
+// a row stride of `stride` elements.  256 threads, 4 x 16 B each.  Rows >= N read as zero.
+__device__ __forceinline__ void load_rows_to_lds(const uint16_t *__restrict__ X, int row0, int N,
+                                                 int H, int head, uint16_t *lds, int stride) {
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int q = threadIdx.x + 256 * p;
+    const int r = q >> 4, c16 = q & 15;
+    const int row = row0 + r;
+    u32x4 x = ldg16(X + ((size_t)row * H + head) * kD + c16 * 8, row < N);
+    *(u32x4 *)(lds + r * stride + c16 * 8) = x;
+  }
+}
+
+// Same block, but stored transposed: lds[c * stride + tr_pos(j)] = X[row0 + j][c].  Each thread
+// loads 4 consecutive rows x 8 columns and writes eight 8-byte groups (4 rows of one column).
+__device__ __forceinline__ void load_rows_to_lds_transposed(const uint16_t *__restrict__ X, int row0,
+                                                            int N, int H, int head, uint16_t *lds,
+                                                            int stride) {
+  const int cc = threadIdx.x & 15, jg = threadIdx.x >> 4;
+  u32x4 x[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = row0 + 4 * jg + r;
+    x[r] = ldg16(X + ((size_t)row * H + head) * kD + cc * 8, row < N);
+  }
+  const int pos = tr_pos(4 * jg);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const int w = e >> 1;
+    u32x2 o;
+    if (e & 1) {
+      o.x = (x[0][w] >> 16) | (x[1][w] & 0xffff0000u);
+      o.y = (x[2][w] >> 16) | (x[3][w] & 0xffff0000u);
+    } else {
+      o.x = (x[0][w] & 0xffffu) | (x[1][w] << 16);
+      o.y = (x[2][w] & 0xffffu) | (x[3][w] << 16);
+    }
+    *(u32x2 *)(lds + (cc * 8 + e) * stride + pos) = o;
+  }
+}
+
+// Epilogue shared by all three kernels: a wave holds a transposed result tile
+//   acc[cb][v] = R[row = lane % 32][col = 32 cb + acc_row(v, half)],   32 rows x 128 cols,
+// multiplies row `lane % 32` by `mul`, and writes rows 0..nrows-1 to out[(row0 + row) * H + head]
+// (a [N, H, 128] tensor) with coalesced stores.  The tile is staged through LDS in two halves of
+// 64 columns; `stage` is this wave's [32][kStageStride] float buffer.  Every wave of the
+// workgroup must call this together (it contains workgroup barriers).
+constexpr int kStageStride = 64 + 4;
+constexpr int kStageFloatsPerWave = 32 * kStageStride;
+
+template <bool kF32Out>
+__device__ __forceinline__ void store_transposed_tile(const f32x16 (&acc)[4], float mul, float *stage,
+                                                      void *out, long long row0, int nrows, int H,
+                                                      int head) {
+  const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int p = 0; p < 2; ++p) {
+    __syncthreads();
+#pragma unroll
+    for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+      for (int q4 = 0; q4 < 4; ++q4) {
+        f32x4 w;
+#pragma unroll
+        for (int b = 0; b < 4; ++b) w[b] = acc[2 * p + cc][4 * q4 + b] * mul;
+        *(f32x4 *)(stage + l32 * kStageStride + cc * 32 + q4 * 8 + half * 4) = w;
+      }
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < 8; ++it) {
+      const int rr = it * 4 + (lane >> 4), c4 = lane & 15;
+      if (rr < nrows) {
+        const f32x4 x = *(const f32x4 *)(stage + rr * kStageStride + c4 * 4);
+        const size_t off = ((size_t)(row0 + rr) * H + head) * kD + p * 64 + c4 * 4;
+        if (kF32Out) {
+          *(f32x4 *)((float *)out + off) = x;
+        } else {
+          u32x2 w;
+          w.x = pack2_bf16(x[0], x[1]);
+          w.y = pack2_bf16(x[2], x[3]);
+          *(u32x2 *)((uint16_t *)out + off) = w;
+        }
+      }
+    }
+  }
+}
+
+}  // namespace va

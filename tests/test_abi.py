@@ -1,0 +1,113 @@
+"""The C-ABI library loads, exports every symbol the header declares, and validates arguments
+on the host (no GPU work is launched by any call in this file)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2407_09105_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2407_09105_amd import build
+        build.build()
+    return binding.lib()
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "varlen_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(va_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_exports_match_header(L):
+    declared = _declared_symbols()
+    assert set(declared) == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_plan_bytes(L):
+    assert L.va_plan_bytes(0, 16) == 0 and L.va_plan_bytes(1, 0) == 0 and L.va_plan_bytes(-1, 4) == 0
+    assert L.va_plan_bytes(65536, 65536) == 0          # N >= 2^31
+    b = L.va_plan_bytes(1, 8192)
+    assert b >= 4 * (8193 + 3 * 8192 + 8 + 2 * 64) and b % 256 == 0
+    assert L.va_plan_bytes(8, 8192) > b
+
+
+def test_bind_validation(L):
+    seg = binding.VaSegments()
+    need = L.va_plan_bytes(2, 100)
+    fake = 0x10000  # never dereferenced: bind is host pointer arithmetic only
+    assert L.va_segments_bind(None, need, 2, 100, C.byref(seg)) == 1
+    assert L.va_segments_bind(fake, need, 0, 100, C.byref(seg)) == 2
+    assert L.va_segments_bind(fake, need - 1, 2, 100, C.byref(seg)) == 4
+    assert L.va_segments_bind(fake + 8, need, 2, 100, C.byref(seg)) == 4      # misaligned
+    assert L.va_segments_bind(fake, need, 2, 100, C.byref(seg)) == 0
+    ptrs = [getattr(seg, f) for f, _ in binding.VaSegments._fields_]
+    assert all(fake <= p < fake + need for p in ptrs) and len(set(ptrs)) == len(ptrs)
+    assert seg.cu_seqlens == fake and seg.seg_id - seg.cu_seqlens >= 4 * 201
+
+
+def _bound(L, rows=1, T=16):
+    seg = binding.VaSegments()
+    assert L.va_segments_bind(0x10000, L.va_plan_bytes(rows, T), rows, T, C.byref(seg)) == 0
+    return seg
+
+
+def test_pack_validation(L):
+    seg = _bound(L)
+    p = 0x20000
+    assert L.va_pack_to_cu_seqlens(None, binding.VA_I64, 1, 16, C.byref(seg), None) == 1
+    assert L.va_pack_to_cu_seqlens(p, binding.VA_I64, 1, 16, None, None) == 1
+    assert L.va_pack_to_cu_seqlens(p, binding.VA_I64, 0, 16, C.byref(seg), None) == 2
+    assert L.va_pack_to_cu_seqlens(p, 7, 1, 16, C.byref(seg), None) == 3
+    assert L.va_pack_to_cu_seqlens(p, binding.VA_I64, 1, 16, C.byref(binding.VaSegments()), None) == 1
+
+
+def test_attn_validation(L):
+    seg = _bound(L)
+    p = 0x20000
+    fwd = lambda *a: L.va_varlen_attn_fwd(*a)
+    ok = [p, p, p, p, p, C.byref(seg), 1, 16, 2, 2, 16, binding.VA_F32, 0.0, None, 0, None]
+
+    def with_(i, val):
+        a = list(ok)
+        a[i] = val
+        return a
+
+    assert fwd(*with_(0, None)) == 1
+    assert fwd(*with_(4, None)) == 1
+    assert fwd(*with_(5, None)) == 1
+    assert fwd(*with_(8, 3)) == 2          # Hq % Hkv != 0
+    assert fwd(*with_(9, 0)) == 2
+    assert fwd(*with_(10, 512)) == 3       # head_dim > 256
+    assert fwd(*with_(11, 9)) == 3         # unknown dtype
+    assert fwd(*with_(6, 0)) == 2
+
+    okb = [p] * 9 + [binding.VA_F32, C.byref(seg), 1, 16, 2, 2, 16, binding.VA_F32, 0.0, p, 1 << 20, None]
+    bwd = lambda *a: L.va_varlen_attn_bwd(*a)
+
+    def withb(i, val):
+        a = list(okb)
+        a[i] = val
+        return a
+
+    assert bwd(*withb(6, None)) == 1
+    assert bwd(*withb(9, 5)) == 3
+    assert bwd(*withb(18, None)) == 1                      # workspace required
+    assert bwd(*withb(19, 16)) == 4                        # workspace too small
+    assert L.va_attn_workspace_bytes(16, 2, 2, 16, 1) >= 16 * 2 * 4
+    assert L.va_attn_workspace_bytes(16, 2, 2, 16, 0) == 0
+    assert L.va_attn_workspace_bytes(0, 2, 2, 16, 1) == 0
+
+
+def test_strings(L):
+    assert L.va_status_string(0) == b"ok"
+    assert all(L.va_status_string(i) for i in range(7))
+    assert b"gfx950" in L.va_version()

@@ -1,0 +1,76 @@
+"""GPU forward/backward vs the oracle, element by element, on seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2407_09105_amd import workloads as wl
+from tests.gpu_util import assert_close, assert_seg_equal, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+def _parity(w, grad_dtype=None, scale=0.0):
+    print(f"case: cfg={w.cfg.name} seed={w.seed} R={w.cfg.rows} T={w.cfg.tokens_per_row} "
+          f"hq={w.cfg.hq} hkv={w.cfg.hkv} d={w.cfg.d} {w.cfg.dtype} grads={grad_dtype}", flush=True)
+    got = run_gpu(w, grad_dtype=grad_dtype, scale=scale)
+    ref = run_oracle(w, scale=None if scale == 0.0 else scale)
+    assert_seg_equal(got["seg"], ref["seg"])
+    stored = ("dQ", "dK", "dV") if grad_dtype == torch.bfloat16 else ()
+    errs = assert_close(got, ref, w.cfg.dtype, bf16_stored=stored)
+    print("   errors (max-abs, rel-L2):", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in errs.items()}, flush=True)
+    return got, ref
+
+
+def test_config1_fp32_smoke():
+    _parity(wl.make_workload(1))
+
+
+@pytest.mark.parametrize("lengths,hq,hkv,d", [
+    ([[4, 8, 5, 11]], 4, 2, 8),
+    ([[1, 1, 30, 2], [20, 14]], 6, 2, 80),
+    ([[70, 1, 129]], 3, 1, 256),
+])
+def test_fp32_generic(lengths, hq, hkv, d):
+    _parity(wl.make_custom(lengths, hq, hkv, d, "f32", seed=5))
+
+
+def test_fp32_explicit_scale():
+    _parity(wl.make_custom([[9, 3, 20]], 2, 2, 32, "f32", seed=6), scale=0.21)
+
+
+def test_bf16_generic_other_head_dim():
+    _parity(wl.make_custom([[40, 7, 81]], 4, 2, 64, "bf16", seed=7), grad_dtype=torch.float32)
+
+
+MFMA_CASES = [
+    # lengths per row, hq, hkv   (d = 128, bf16 -> MFMA kernels)
+    ([[3, 5, 1, 7]], 2, 2),                               # one partial tile
+    ([[128]], 1, 1),                                      # exactly one tile, one example
+    ([[64, 64, 128, 1, 127]], 2, 1),                      # boundaries on tile / block edges
+    ([[300, 45, 1, 1, 200, 93]], 4, 2),                   # several tiles, ragged tail (640 tokens)
+    ([[100, 219], [319], [1] * 319], 2, 2),               # 3 rows, T = 319 (not a multiple of 64)
+    ([[513, 31, 480]], 5, 1),                             # G = 5 (not a power of two), 1024 tokens
+    ([[17] * 30 + [2]], 2, 2),                            # many short examples per tile
+]
+
+
+@pytest.mark.parametrize("lengths,hq,hkv", MFMA_CASES)
+def test_bf16_mfma_fp32_grads(lengths, hq, hkv):
+    _parity(wl.make_custom(lengths, hq, hkv, 128, "bf16", seed=11), grad_dtype=torch.float32)
+
+
+@pytest.mark.parametrize("lengths,hq,hkv", [MFMA_CASES[3], MFMA_CASES[4]])
+def test_bf16_mfma_bf16_grads(lengths, hq, hkv):
+    _parity(wl.make_custom(lengths, hq, hkv, 128, "bf16", seed=12), grad_dtype=torch.bfloat16)
+
+
+def test_bf16_mfma_explicit_scale():
+    _parity(wl.make_custom([[200, 56]], 2, 2, 128, "bf16", seed=13), grad_dtype=torch.float32, scale=0.05)
+
+
+def test_bwd_is_deterministic():
+    w = wl.make_custom([[300, 45, 1, 1, 200, 93]], 4, 2, 128, "bf16", seed=14)
+    a = run_gpu(w, grad_dtype=torch.float32)
+    b = run_gpu(w, grad_dtype=torch.float32)
+    for key in ("O", "LSE", "dQ", "dK", "dV"):
+        assert np.array_equal(a[key], b[key]), key

@@ -1,0 +1,92 @@
+"""GPU boundary scan vs the oracle: bit-exact (integer work)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2407_09105_amd import binding, workloads as wl
+from tests.gpu_util import DEV, assert_seg_equal
+
+pytestmark = pytest.mark.gpu
+
+
+def _gpu_pack(pos_np, dtype=torch.int64):
+    pos = torch.from_numpy(pos_np).to(DEV).to(dtype)
+    seg = binding.pack_to_cu_seqlens(pos)
+    torch.cuda.synchronize()
+    return seg.host()
+
+
+def _check_orders(got, pos_np):
+    R, T = pos_np.shape
+    ref = oracle.pack(pos_np)
+    tpr = (T + 127) // 128
+    nt = R * tpr
+    tiles = np.arange(nt)
+    t0 = (tiles // tpr) * T + (tiles % tpr) * 128
+    t1 = np.minimum(t0 + 128, (tiles // tpr + 1) * T) - 1
+    cost_q = (t1 >> 6) - (ref["seg_start"][t0] >> 6) + 1
+    cost_kv = ((ref["seg_end"][t1] - 1) >> 6) - (t0 >> 6) + 1
+    for name, cost in (("q_tile_order", cost_q), ("kv_tile_order", cost_kv)):
+        order = got[name]
+        assert sorted(order.tolist()) == list(range(nt)), name     # a permutation of the tiles
+        c = cost[order]
+        assert np.all(c[:-1] >= c[1:]), name                       # heaviest first
+        # ties keep index order: the result is unique
+        expect = np.lexsort((tiles, -cost))
+        assert np.array_equal(order, expect), name
+
+
+def test_worked_example(worked_example):
+    pos = np.array([worked_example["position_ids"]], dtype=np.int64)
+    got = _gpu_pack(pos)
+    assert got["cu_seqlens"].tolist() == worked_example["cu_seqlens"]
+    assert got["n"] == 4 and got["max_seqlen"] == 11
+    assert_seg_equal(got, oracle.pack(pos))
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+@pytest.mark.parametrize("dtype", [torch.int64, torch.int32])
+def test_configs(cfg, dtype):
+    w = wl.make_workload(cfg, tensors=False)
+    got = _gpu_pack(w.position_ids, dtype)
+    assert_seg_equal(got, oracle.pack(w.position_ids))
+    _check_orders(got, w.position_ids)
+
+
+@pytest.mark.parametrize("R,T,maxlen,seed", [
+    (1, 1, 1, 0), (1, 7, 3, 1), (3, 129, 40, 2), (2, 2048, 300, 3), (5, 2049, 17, 4),
+    (1, 4097, 5000, 5), (7, 1000, 1, 6), (2, 70001, 900, 7), (1, 300000, 2500, 8),
+])
+def test_ragged_shapes(R, T, maxlen, seed):
+    rng = np.random.default_rng(seed)
+    rows = []
+    for _ in range(R):
+        row, left = [], T
+        while left > 0:
+            L = int(rng.integers(1, min(left, maxlen) + 1))
+            row.append(L)
+            left -= L
+        rows.append(row)
+    pos = wl.position_ids_from_lengths(rows)
+    got = _gpu_pack(pos)
+    assert_seg_equal(got, oracle.pack(pos))
+    _check_orders(got, pos)
+
+
+def test_rows_not_starting_at_zero_and_odd_ids():
+    pos = np.array([[0, 1, 2, 3, 0, 1], [5, 6, 7, 0, 1, 2], [3, 3, 3, 3, -1, 9]], dtype=np.int64)
+    got = _gpu_pack(pos)
+    assert got["cu_seqlens"].tolist() == [0, 4, 6, 9, 12, 18]
+    assert_seg_equal(got, oracle.pack(pos))
+
+
+def test_pack_twice_into_same_plan():
+    # the plan buffer is reusable: a second pack overwrites every field
+    w4 = wl.make_workload(4, tensors=False)
+    pos_a = torch.from_numpy(w4.position_ids).to(DEV)
+    seg = binding.pack_to_cu_seqlens(pos_a)
+    one = np.tile(np.arange(8192, dtype=np.int64), (8, 1))
+    binding.pack_to_cu_seqlens(torch.from_numpy(one).to(DEV), seg)
+    torch.cuda.synchronize()
+    assert_seg_equal(seg.host(), oracle.pack(one))
