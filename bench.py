@@ -1,0 +1,250 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed variable-length attention hot path on one MI355X.
+
+One "step" = one pass of the whole path over one packed batch resident in HBM:
+position_ids -> cu_seqlens / tile schedule, forward (O, LSE), backward (dQ, dK, dV).
+
+Prints ONE JSON line: useful (mask-respecting, padding-free) attention TFLOP/s of
+fwd+bwd on the workload, plus tokens/s, the same kernels on the equivalent padded
+batch, the roofline fraction of the dominant kernel, and the CPU oracle timed on
+a bounded sample of the same workload as a baseline.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0   # MI355X dense bf16 matrix peak (published)
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E peak (published)
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload (index into the config table, 2..5)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-padded", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=0, help="query heads in the CPU-oracle sample (0 = auto)")
+    return ap.parse_args()
+
+
+def flops(cfg, pairs):
+    """Useful FLOPs: 4d per unmasked (i, j) pair per query head forward, 10d backward."""
+    f = 4 * cfg.d * cfg.hq * pairs
+    b = 10 * cfg.d * cfg.hq * pairs
+    return f, b
+
+
+class GpuRun:
+    """Device buffers + one `step()` of the path; stage events for per-kernel timing."""
+
+    def __init__(self, torch, binding, pos_np, q, k, v, do):
+        self.torch, self.b = torch, binding
+        self.pos = torch.from_numpy(pos_np).cuda()
+        self.q, self.k, self.v, self.do = q, k, v, do
+        self.seg = binding.Segments(pos_np.shape[0], pos_np.shape[1], "cuda")
+        self.o = torch.empty_like(q)
+        self.lse = torch.empty((q.shape[1], q.shape[0]), dtype=torch.float32, device="cuda")
+        self.dq, self.dk, self.dv = torch.empty_like(q), torch.empty_like(k), torch.empty_like(v)
+        self.ws = binding.bwd_workspace(q, k)
+
+    def step(self, ev=None):
+        b = self.b
+        if ev: ev[0].record()
+        b.pack_to_cu_seqlens(self.pos, self.seg)
+        if ev: ev[1].record()
+        b.varlen_attn_fwd(self.q, self.k, self.v, self.seg, out=self.o, lse=self.lse)
+        if ev: ev[2].record()
+        if ev:
+            for i, stage in enumerate((b.STAGE_D, b.STAGE_DKDV, b.STAGE_DQ)):
+                b.varlen_attn_bwd(self.do, self.q, self.k, self.v, self.o, self.lse, self.seg, dq=self.dq,
+                                  dk=self.dk, dv=self.dv, workspace=self.ws, stages=stage)
+                ev[3 + i].record()
+        else:
+            b.varlen_attn_bwd(self.do, self.q, self.k, self.v, self.o, self.lse, self.seg, dq=self.dq,
+                              dk=self.dk, dv=self.dv, workspace=self.ws)
+
+
+def timed(torch, run, steps, warmup, with_events=True):
+    """W warm-up steps, then exactly K timed steps between device synchronisations.
+    Returns (ms_per_step, {stage: avg ms}) -- stage times from events recorded inside the timed steps
+    on the stream the kernels are launched on (torch's current stream, whose handle the binding passes)."""
+    for _ in range(warmup):
+        run.step()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(steps)] if with_events else None
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        run.step(evs[s] if evs else None)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    stages = {}
+    if evs:
+        names = ["pack", "fwd", "bwd_D", "bwd_dKdV", "bwd_dQ"]
+        for i, n in enumerate(names):
+            stages[n] = float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs]))
+    return ms, stages
+
+
+def padded_run(torch, binding, wl, w, q, k, v, do):
+    """Batch-level padding of the same examples: groups of 4, each right-padded to the group's
+    longest (a (4, L_max) batch per group); run as examples of uniform length through the same
+    kernels.  Pad tokens hold zeros.  Useful FLOPs and tokens counted are the real ones."""
+    lay = wl.padded_layout(w.lengths, group=4)
+    n_pad = sum(p for _, p in lay)
+    pos = np.concatenate([np.arange(p, dtype=np.int64) for _, p in lay])[None, :]
+    src = np.concatenate([np.arange(L, dtype=np.int64) for L, _ in lay])            # offsets inside example
+    starts_real = np.cumsum([0] + [L for L, _ in lay])[:-1]
+    starts_pad = np.cumsum([0] + [p for _, p in lay])[:-1]
+    idx_real = np.concatenate([s + np.arange(L) for s, (L, _) in zip(starts_real, lay)])
+    idx_pad = np.concatenate([s + np.arange(L) for s, (L, _) in zip(starts_pad, lay)])
+    del src
+    ir = torch.from_numpy(idx_real).cuda()
+    ip = torch.from_numpy(idx_pad).cuda()
+
+    def pad(t):
+        out = torch.zeros((n_pad,) + tuple(t.shape[1:]), dtype=t.dtype, device="cuda")
+        out[ip] = t[ir]
+        return out
+
+    run = GpuRun(torch, binding, pos, pad(q), pad(k), pad(v), pad(do))
+    return run, n_pad, ir, ip
+
+
+def cpu_baseline(wl, cfg_id, heads):
+    """The oracle as it stands, timed on the host cores, on a bounded sample of the workload:
+    the same packed rows and lengths with fewer heads (work is exactly linear in heads)."""
+    from oracle import oracle
+    cfg = wl.CONFIGS[cfg_id]
+    G = cfg.hq // cfg.hkv
+    hkv_s = max(1, heads // G)
+    hq_s = hkv_s * G
+    w = wl.make_workload(cfg_id, hq=hq_s, hkv=hkv_s)
+    seg = oracle.pack(w.position_ids)
+    t0 = time.perf_counter()
+    oracle.fwd(w.q, w.k, w.v, seg["cu_seqlens"])
+    oracle.bwd(w.do, w.q, w.k, w.v, seg["cu_seqlens"])
+    dt = time.perf_counter() - t0
+    f, b = flops(w.cfg, w.stats["pairs"])
+    return {
+        "value": (f + b) / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"{hq_s} of {cfg.hq} query heads ({hkv_s} of {cfg.hkv} KV heads) of the same packed batch, "
+                  f"fwd+bwd in fp64, {dt:.1f} s; work is linear in heads",
+        "tokens_per_s_equiv": cfg.n_tokens / (dt * cfg.hq / hq_s),
+    }
+
+
+def read_traffic(cfg_id, kernel):
+    """HBM bytes per launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_cfg{cfg_id}.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 2 and parts[0] == kernel + ":":
+            try:
+                return float(parts[1])
+            except ValueError:
+                return None
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (one process, no collectives); "
+              f"--gpus {args.gpus} is not supported. Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2407_09105_amd import binding, workloads as wl
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    binding.lib()  # fail loudly if the HIP library is not built
+
+    cfg_id = args.config
+    w = wl.make_workload(cfg_id)
+    cfg = w.cfg
+    assert cfg.dtype == "bf16"
+    to_dev = lambda a: torch.from_numpy(a).cuda().to(torch.bfloat16)
+    q, k, v, do = to_dev(w.q), to_dev(w.k), to_dev(w.v), to_dev(w.do)
+
+    run = GpuRun(torch, binding, w.position_ids, q, k, v, do)
+    ms, stages = timed(torch, run, args.steps, args.warmup)
+    # the same K steps without stage events (the figure reported as `value`)
+    ms_plain, _ = timed(torch, run, args.steps, 2, with_events=False)
+    f_fwd, f_bwd = flops(cfg, w.stats["pairs"])
+    useful = f_fwd + f_bwd
+    value = useful / (ms_plain * 1e-3) / 1e12
+
+    # dominant kernel -> roofline.  Algorithmic FLOPs per pair per head: forward 4d; the backward's
+    # 10d split as 8d to the dK/dV kernel (S, dP, dV, dK) and 2d to the dQ kernel (dQ; its own
+    # recomputation of S and dP is overhead, not algorithmic work).
+    pairs_h = w.stats["pairs"] * cfg.hq
+    algo = {"fwd": 4 * cfg.d * pairs_h, "bwd_dKdV": 8 * cfg.d * pairs_h, "bwd_dQ": 2 * cfg.d * pairs_h}
+    kernel_names = {"fwd": "fwd_mfma_kernel", "bwd_dKdV": "dkdv_mfma_kernel", "bwd_dQ": "dq_mfma_kernel"}
+    dom = max(algo, key=lambda s: stages[s])
+    achieved = algo[dom] / (stages[dom] * 1e-3) / 1e12
+    roofline = {
+        "kernel": kernel_names[dom], "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS,
+        "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
+        "traffic": read_traffic(cfg_id, kernel_names[dom]),
+        "avg_kernel_ms": stages[dom],
+        "all_kernels": {kernel_names[s]: {"ms": stages[s], "algorithmic_TFLOPs": algo[s] / (stages[s] * 1e-3) / 1e12,
+                                          "frac_of_bf16_mfma_peak": algo[s] / (stages[s] * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS}
+                        for s in algo},
+    }
+    # minimum HBM traffic of the whole step (each tensor once) -> fraction of the HBM roofline
+    e = 2
+    hbm_min = cfg.n_tokens * (6 * e * cfg.d * (cfg.hq + cfg.hkv) + 12 * cfg.hq)
+    out = {
+        "metric": "useful attention TFLOP/s (fwd+bwd), packed, one GPU",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_plain, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"configs[{cfg_id - 1}] {cfg.name}: {cfg.rows} packed row(s) x {cfg.tokens_per_row} tokens, "
+                               f"Hq={cfg.hq} Hkv={cfg.hkv} d={cfg.d}, seed {w.seed}",
+                   "n_tokens": cfg.n_tokens, "n_examples": w.stats["n_segments"], "len_min": w.stats["len_min"],
+                   "len_median": w.stats["len_median"], "len_max": w.stats["len_max"], "pairs_per_head": w.stats["pairs"],
+                   "grad_dtype": "bf16"},
+        "tokens_per_s": cfg.n_tokens / (ms_plain * 1e-3),
+        "frac_bf16_mfma_peak": value / PEAK_BF16_MFMA_TFLOPS,
+        "frac_hbm_peak_at_min_traffic": hbm_min / (ms_plain * 1e-3) / 1e9 / PEAK_HBM_GBS,
+        "stage_ms": stages, "ms_per_step_with_stage_events": ms,
+        "useful_gflop": {"fwd": f_fwd / 1e9, "bwd": f_bwd / 1e9},
+        "roofline": roofline,
+    }
+
+    if not args.no_padded:
+        prun, n_pad, _, _ = padded_run(torch, binding, wl, w, q, k, v, do)
+        pms, _ = timed(torch, prun, max(5, args.steps // 2), 3, with_events=False)
+        out["padded"] = {
+            "layout": "groups of 4 examples, each right-padded to the group's longest (batch-level padding)",
+            "padded_tokens": n_pad, "ms_per_step": pms, "value": useful / (pms * 1e-3) / 1e12, "unit": "TFLOP/s (useful)",
+            "tokens_per_s": cfg.n_tokens / (pms * 1e-3), "packing_gain": pms / ms_plain,
+        }
+        del prun
+    if not args.no_cpu_baseline:
+        heads = args.cpu_heads or {2: 16, 3: 8, 4: 16, 5: 0}.get(cfg_id, 8)
+        if heads:
+            out["cpu_baseline"] = cpu_baseline(wl, cfg_id, heads)
+        else:
+            out["cpu_baseline"] = None
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -125,6 +125,23 @@ va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const
                              va_dtype dt, float softmax_scale, void *workspace,
                              size_t workspace_bytes, void *stream);
 
+/*
+ * The backward is three kernels: D = rowsum(dO * O), then dK/dV, then dQ.  This variant runs only
+ * the ones selected by `stages` (an OR of the flags below), so that a caller can time them one by
+ * one with events on `stream`.  Running all three flags in order gives exactly va_varlen_attn_bwd;
+ * VA_STAGE_DKDV and VA_STAGE_DQ read the D that an earlier VA_STAGE_D call left in `workspace`.
+ * Arguments, validation and errors as va_varlen_attn_bwd; stages == 0 or unknown bits: VA_ERR_UNSUPPORTED.
+ */
+#define VA_STAGE_D 1u
+#define VA_STAGE_DKDV 2u
+#define VA_STAGE_DQ 4u
+va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K, const void *V,
+                                    const void *O, const float *LSE, void *dQ, void *dK, void *dV,
+                                    va_dtype grad_dt, const va_segments *seg, int32_t rows,
+                                    int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
+                                    va_dtype dt, float softmax_scale, void *workspace,
+                                    size_t workspace_bytes, void *stream, uint32_t stages);
+
 /* Static string for a status code. */
 const char *va_status_string(va_status s);
 

@@ -20,10 +20,11 @@ VA_OK = 0
 VA_F32, VA_BF16 = 0, 1
 VA_I32, VA_I64 = 0, 1
 VA_TILE = 128
+STAGE_D, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 
 EXPORTS = (
     "va_plan_bytes", "va_segments_bind", "va_pack_to_cu_seqlens", "va_attn_workspace_bytes",
-    "va_varlen_attn_fwd", "va_varlen_attn_bwd", "va_status_string", "va_version",
+    "va_varlen_attn_fwd", "va_varlen_attn_bwd", "va_varlen_attn_bwd_stages", "va_status_string", "va_version",
 )
 
 
@@ -59,6 +60,8 @@ def lib() -> C.CDLL:
     L.va_varlen_attn_bwd.restype = C.c_int
     L.va_varlen_attn_bwd.argtypes = [C.c_void_p] * 9 + [C.c_int, C.POINTER(VaSegments)] + [C.c_int32] * 5 + [
         C.c_int, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
+    L.va_varlen_attn_bwd_stages.restype = C.c_int
+    L.va_varlen_attn_bwd_stages.argtypes = L.va_varlen_attn_bwd.argtypes + [C.c_uint32]
     L.va_status_string.restype = C.c_char_p
     L.va_status_string.argtypes = [C.c_int]
     L.va_version.restype = C.c_char_p
@@ -200,8 +203,10 @@ def bwd_workspace(q, k) -> torch.Tensor:
 
 
 def varlen_attn_bwd(do, q, k, v, o, lse, seg: Segments, softmax_scale: float = 0.0,
-                    grad_dtype: Optional[torch.dtype] = None, dq=None, dk=None, dv=None, workspace=None):
-    """-> dQ [N, Hq, d], dK, dV [N, Hkv, d] in grad_dtype (default: dtype of q)."""
+                    grad_dtype: Optional[torch.dtype] = None, dq=None, dk=None, dv=None, workspace=None,
+                    stages: Optional[int] = None):
+    """-> dQ [N, Hq, d], dK, dV [N, Hkv, d] in grad_dtype (default: dtype of q).
+    `stages` (an OR of STAGE_D, STAGE_DKDV, STAGE_DQ) runs only those kernels of the backward."""
     _need_cuda(do, q, k, v, o, lse)
     N, hq, hkv, d = _shapes(q, k, v, seg)
     if not (q.dtype == k.dtype == v.dtype == o.dtype == do.dtype):
@@ -213,8 +218,11 @@ def varlen_attn_bwd(do, q, k, v, o, lse, seg: Segments, softmax_scale: float = 0
     dk = torch.empty(k.shape, dtype=gdt, device=q.device) if dk is None else dk
     dv = torch.empty(v.shape, dtype=gdt, device=q.device) if dv is None else dv
     ws = bwd_workspace(q, k) if workspace is None else workspace
-    _check("va_varlen_attn_bwd", lib().va_varlen_attn_bwd(
-        do.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
-        dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _dt(dq), C.byref(seg.c), seg.rows, seg.tokens_per_row,
-        hq, hkv, d, _dt(q), float(softmax_scale), ws.data_ptr(), ws.numel() * 4, _stream()))
+    args = [do.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+            dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _dt(dq), C.byref(seg.c), seg.rows, seg.tokens_per_row,
+            hq, hkv, d, _dt(q), float(softmax_scale), ws.data_ptr(), ws.numel() * 4, _stream()]
+    if stages is None:
+        _check("va_varlen_attn_bwd", lib().va_varlen_attn_bwd(*args))
+    else:
+        _check("va_varlen_attn_bwd_stages", lib().va_varlen_attn_bwd_stages(*args, int(stages)))
     return dq, dk, dv

@@ -120,16 +120,17 @@ va_status va_varlen_attn_fwd(const void *Q, const void *K, const void *V, void *
   return e == hipSuccess ? VA_OK : VA_ERR_HIP;
 }
 
-va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const void *V,
-                             const void *O, const float *LSE, void *dQ, void *dK, void *dV,
-                             va_dtype grad_dt, const va_segments *seg, int32_t rows,
-                             int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
-                             va_dtype dt, float softmax_scale, void *workspace,
-                             size_t workspace_bytes, void *stream) {
+va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K, const void *V,
+                                    const void *O, const float *LSE, void *dQ, void *dK, void *dV,
+                                    va_dtype grad_dt, const va_segments *seg, int32_t rows,
+                                    int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
+                                    va_dtype dt, float softmax_scale, void *workspace,
+                                    size_t workspace_bytes, void *stream, uint32_t stages) {
   if (!dO || !Q || !K || !V || !O || !LSE || !dQ || !dK || !dV) return VA_ERR_NULL;
   va_status s = check_common(seg, rows, tokens_per_row, hq, hkv, d, dt);
   if (s != VA_OK) return s;
   if (grad_dt != VA_F32 && grad_dt != VA_BF16) return VA_ERR_UNSUPPORTED;
+  if (stages == 0 || (stages & ~(VA_STAGE_D | VA_STAGE_DKDV | VA_STAGE_DQ))) return VA_ERR_UNSUPPORTED;
   const int N = rows * tokens_per_row;
   const size_t need = va_attn_workspace_bytes(N, hq, hkv, d, 1);
   if (!workspace) return VA_ERR_NULL;
@@ -137,14 +138,29 @@ va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
   float *delta = (float *)workspace;
   hipStream_t st = (hipStream_t)stream;
-  hipError_t e = va::launch_delta(dO, O, delta, N, hq, d, dt, st);
+  hipError_t e = hipSuccess;
+  if (stages & VA_STAGE_D) e = va::launch_delta(dO, O, delta, N, hq, d, dt, st);
   if (e != hipSuccess) return VA_ERR_HIP;
-  if (use_mfma(dt, d))
-    e = va::launch_mfma_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, rows, tokens_per_row, hq,
-                            hkv, scale, st);
-  else
-    e = va::launch_generic_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, N, hq, hkv, d, dt, scale, st);
+  if (stages & (VA_STAGE_DKDV | VA_STAGE_DQ)) {
+    if (use_mfma(dt, d))
+      e = va::launch_mfma_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, rows, tokens_per_row, hq,
+                              hkv, scale, st, stages);
+    else
+      e = va::launch_generic_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, N, hq, hkv, d, dt, scale,
+                                 st, stages);
+  }
   return e == hipSuccess ? VA_OK : VA_ERR_HIP;
+}
+
+va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const void *V,
+                             const void *O, const float *LSE, void *dQ, void *dK, void *dV,
+                             va_dtype grad_dt, const va_segments *seg, int32_t rows,
+                             int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
+                             va_dtype dt, float softmax_scale, void *workspace,
+                             size_t workspace_bytes, void *stream) {
+  return va_varlen_attn_bwd_stages(dO, Q, K, V, O, LSE, dQ, dK, dV, grad_dt, seg, rows, tokens_per_row, hq,
+                                   hkv, d, dt, softmax_scale, workspace, workspace_bytes, stream,
+                                   VA_STAGE_D | VA_STAGE_DKDV | VA_STAGE_DQ);
 }
 
 const char *va_status_string(va_status s) {

@@ -252,7 +252,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const void *V,
                            const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
                            va_dtype grad_dt, const va_segments &seg, int rows, int T, int hq,
-                           int hkv, float scale, hipStream_t stream) {
+                           int hkv, float scale, hipStream_t stream, unsigned stages) {
   const int tiles_per_row = ceil_div(T, kBT);
   const long long ntiles = (long long)rows * tiles_per_row;
   if (ntiles * hq > 0x7fffffffll) return hipErrorInvalidValue;
@@ -261,18 +261,19 @@ hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const v
   const uint16_t *q = (const uint16_t *)Q, *k = (const uint16_t *)K, *v = (const uint16_t *)V,
                  *g = (const uint16_t *)dO;
   const unsigned gq = (unsigned)(ntiles * hq), gkv = (unsigned)(ntiles * hkv);
+  const bool do_kv = stages & VA_STAGE_DKDV, do_q = stages & VA_STAGE_DQ;
   if (grad_dt == VA_F32) {
-    dkdv_mfma_kernel<true><<<gkv, 256, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
+    if (do_kv) dkdv_mfma_kernel<true><<<gkv, 256, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
                                                     seg.kv_tile_order, N, T, tiles_per_row, hq, hkv,
                                                     scale_log2, scale);
-    dq_mfma_kernel<true><<<gq, 256, 0, stream>>>(g, q, k, v, LSE, delta, dQ, seg.seg_start,
+    if (do_q) dq_mfma_kernel<true><<<gq, 256, 0, stream>>>(g, q, k, v, LSE, delta, dQ, seg.seg_start,
                                                  seg.q_tile_order, N, T, tiles_per_row, hq, hkv,
                                                  scale_log2, scale);
   } else {
-    dkdv_mfma_kernel<false><<<gkv, 256, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
+    if (do_kv) dkdv_mfma_kernel<false><<<gkv, 256, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
                                                      seg.kv_tile_order, N, T, tiles_per_row, hq, hkv,
                                                      scale_log2, scale);
-    dq_mfma_kernel<false><<<gq, 256, 0, stream>>>(g, q, k, v, LSE, delta, dQ, seg.seg_start,
+    if (do_q) dq_mfma_kernel<false><<<gq, 256, 0, stream>>>(g, q, k, v, LSE, delta, dQ, seg.seg_start,
                                                   seg.q_tile_order, N, T, tiles_per_row, hq, hkv,
                                                   scale_log2, scale);
   }

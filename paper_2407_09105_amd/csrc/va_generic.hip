@@ -221,10 +221,12 @@ hipError_t launch_delta(const void *dO, const void *O, float *delta, int N, int 
 template <typename T, typename TG>
 static void launch_bwd_t(const void *dO, const void *Q, const void *K, const void *V, const float *LSE,
                          const float *delta, void *dQ, void *dK, void *dV, const va_segments &seg,
-                         int N, int hq, int hkv, int d, float scale, hipStream_t stream) {
+                         int N, int hq, int hkv, int d, float scale, hipStream_t stream, unsigned stages) {
+  if (stages & VA_STAGE_DQ)
   generic_dq_kernel<T, TG><<<blocks_for((long long)N * hq), 256, 0, stream>>>(
       (const T *)dO, (const T *)Q, (const T *)K, (const T *)V, LSE, delta, (TG *)dQ, seg.seg_start, N, hq,
       hkv, d, scale);
+  if (stages & VA_STAGE_DKDV)
   generic_dkv_kernel<T, TG><<<blocks_for((long long)N * hkv), 256, 0, stream>>>(
       (const T *)dO, (const T *)Q, (const T *)K, (const T *)V, LSE, delta, (TG *)dK, (TG *)dV, seg.seg_end,
       N, hq, hkv, d, scale);
@@ -233,15 +235,15 @@ static void launch_bwd_t(const void *dO, const void *Q, const void *K, const voi
 hipError_t launch_generic_bwd(const void *dO, const void *Q, const void *K, const void *V,
                               const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
                               va_dtype grad_dt, const va_segments &seg, int N, int hq, int hkv,
-                              int d, va_dtype dt, float scale, hipStream_t stream) {
+                              int d, va_dtype dt, float scale, hipStream_t stream, unsigned stages) {
   if (dt == VA_F32 && grad_dt == VA_F32)
-    launch_bwd_t<float, float>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream);
+    launch_bwd_t<float, float>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream, stages);
   else if (dt == VA_F32)
-    launch_bwd_t<float, uint16_t>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream);
+    launch_bwd_t<float, uint16_t>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream, stages);
   else if (grad_dt == VA_F32)
-    launch_bwd_t<uint16_t, float>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream);
+    launch_bwd_t<uint16_t, float>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream, stages);
   else
-    launch_bwd_t<uint16_t, uint16_t>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream);
+    launch_bwd_t<uint16_t, uint16_t>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream, stages);
   return hipGetLastError();
 }
 

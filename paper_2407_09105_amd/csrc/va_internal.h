@@ -25,7 +25,7 @@ hipError_t launch_delta(const void *dO, const void *O, float *delta, int N, int 
 hipError_t launch_generic_bwd(const void *dO, const void *Q, const void *K, const void *V,
                               const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
                               va_dtype grad_dt, const va_segments &seg, int N, int hq, int hkv,
-                              int d, va_dtype dt, float scale, hipStream_t stream);
+                              int d, va_dtype dt, float scale, hipStream_t stream, unsigned stages);
 
 // va_fwd_mfma.hip / va_bwd_mfma.hip : bf16, head_dim 128
 hipError_t launch_mfma_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
@@ -34,6 +34,6 @@ hipError_t launch_mfma_fwd(const void *Q, const void *K, const void *V, void *O,
 hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const void *V,
                            const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
                            va_dtype grad_dt, const va_segments &seg, int rows, int T, int hq,
-                           int hkv, float scale, hipStream_t stream);
+                           int hkv, float scale, hipStream_t stream, unsigned stages);
 
 }  // namespace va

@@ -1,0 +1,140 @@
+"""Parity at the full sizes of the benchmark configurations, through the same calls and launch
+configuration bench.py times.
+
+Config 2 (the benchmarked workload) is compared element by element against the full oracle.
+Configs 3-5 are compared on sampled output rows the oracle computes one by one (forward rows,
+dQ rows, dK/dV rows), plus properties that hold at any size.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2407_09105_amd import binding, workloads as wl
+from tests.gpu_util import (BF16_MAX_ABS, BF16_REL_L2, DEV, assert_close, assert_seg_equal, max_abs, rel_l2,
+                            run_gpu, run_oracle, to_dev)
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config2_full_elementwise():
+    w = wl.make_workload(2)
+    print("config 2:", w.stats, flush=True)
+    got = run_gpu(w, grad_dtype=torch.float32)
+    ref = run_oracle(w)
+    assert_seg_equal(got["seg"], ref["seg"])
+    errs = assert_close(got, ref, "bf16")
+    print("   errors (max-abs, rel-L2):", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in errs.items()}, flush=True)
+
+
+def _sample_kv(rng, cu, n_cheap, n_costly, cheap_cap=5e5, costly_cap=1e7):
+    """Key rows to check: cost of one dK/dV row ~ (rows after j) x (example length)."""
+    N = int(cu[-1])
+    seg_of = np.searchsorted(cu, np.arange(N), side="right") - 1
+    a, b = cu[seg_of], cu[seg_of + 1]
+    cost = (b - np.arange(N)).astype(np.float64) * (b - a)
+    cheap = np.flatnonzero(cost <= cheap_cap)
+    costly = np.flatnonzero((cost > cheap_cap) & (cost <= costly_cap))
+    pick = list(rng.choice(cheap, size=min(n_cheap, cheap.size), replace=False))
+    if costly.size:
+        pick += list(rng.choice(costly, size=min(n_costly, costly.size), replace=False))
+    return np.array(sorted(pick), dtype=np.int32)
+
+
+@pytest.mark.parametrize("cfg_id", [3, 4, 5])
+def test_sampled_rows_full_size(cfg_id):
+    w = wl.make_workload(cfg_id)
+    cfg = w.cfg
+    print(f"config {cfg_id}:", w.stats, flush=True)
+    pos = torch.from_numpy(w.position_ids).to(DEV)
+    q, k, v, do = (to_dev(a, "bf16") for a in (w.q, w.k, w.v, w.do))
+    seg = binding.pack_to_cu_seqlens(pos)
+    o, lse = binding.varlen_attn_fwd(q, k, v, seg)
+    dq, dk, dv = binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, grad_dtype=torch.float32)
+    torch.cuda.synchronize()
+    ref_seg = oracle.pack(w.position_ids)
+    assert_seg_equal(seg.host(), ref_seg)
+    cu = ref_seg["cu_seqlens"]
+
+    rng = np.random.default_rng(1000 + cfg_id)
+    N = cfg.n_tokens
+    # query-side samples: uniform rows + the last row of each of the longest examples + tile edges
+    tok = list(rng.integers(0, N, size=300))
+    longest = np.argsort(-np.diff(cu))[:4]
+    tok += [int(cu[s + 1] - 1) for s in longest] + [int(cu[s]) for s in longest]
+    tok += [127, 128, N - 1, N - 128, cfg.tokens_per_row - 1, cfg.tokens_per_row % N]
+    tok = np.array(tok, dtype=np.int32)
+    head = rng.integers(0, cfg.hq, size=tok.size).astype(np.int32)
+    Or, LSEr, dQr = oracle.rows_q(w.do, w.q, w.k, w.v, cu, tok, head)
+    t_idx, h_idx = torch.from_numpy(tok.astype(np.int64)).to(DEV), torch.from_numpy(head.astype(np.int64)).to(DEV)
+    f = lambda t: t.float().cpu().numpy().astype(np.float64)
+    got_O, got_dQ, got_LSE = f(o[t_idx, h_idx]), f(dq[t_idx, h_idx]), f(lse[h_idx, t_idx])
+    e = {"O": (max_abs(got_O, Or), rel_l2(got_O, Or)), "dQ": (max_abs(got_dQ, dQr), rel_l2(got_dQ, dQr)),
+         "LSE": (max_abs(got_LSE, LSEr), 0.0)}
+
+    jt = _sample_kv(rng, cu, n_cheap=96, n_costly=8)
+    jh = rng.integers(0, cfg.hkv, size=jt.size).astype(np.int32)
+    dKr, dVr = oracle.rows_kv(w.do, w.q, w.k, w.v, cu, jt, jh)
+    j_idx, g_idx = torch.from_numpy(jt.astype(np.int64)).to(DEV), torch.from_numpy(jh.astype(np.int64)).to(DEV)
+    got_dK, got_dV = f(dk[j_idx, g_idx]), f(dv[j_idx, g_idx])
+    e["dK"] = (max_abs(got_dK, dKr), rel_l2(got_dK, dKr))
+    e["dV"] = (max_abs(got_dV, dVr), rel_l2(got_dV, dVr))
+    print("   sampled errors (max-abs, rel-L2):", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in e.items()}, flush=True)
+    for key in ("O", "dQ", "dK", "dV"):
+        assert e[key][0] <= BF16_MAX_ABS and e[key][1] <= BF16_REL_L2, (key, e)
+    assert e["LSE"][0] <= 1e-3, e
+
+    # properties that hold at any size
+    for t in (o, lse, dq, dk, dv):
+        assert bool(torch.isfinite(t).all())
+    # a length-1 example outputs its own V, and gets dQ = dK = 0
+    ones = np.flatnonzero(np.diff(cu) == 1)
+    if ones.size:
+        t1 = torch.from_numpy(cu[ones].astype(np.int64)).to(DEV)
+        G = cfg.hq // cfg.hkv
+        assert torch.equal(o[t1], v[t1].repeat_interleave(G, dim=1))
+        assert float(dq[t1].abs().max()) == 0.0 and float(dk[t1].abs().max()) == 0.0
+    # D identity: sum_c dQ_i . q_i == sum_c dK ... (softmax rows sum to one => sum_j dS_ij = 0) is not
+    # directly observable; instead check the per-head identity  sum_i dQ_i.q_i = sum_j dK_j.k_j  per example
+    # for MHA (each equals scale * sum_ij dS_ij S_ij / scale)
+    if cfg.hq == cfg.hkv:
+        lhs = (dq.double() * q.double()).sum(dim=(1, 2))
+        rhs = (dk.double() * k.double()).sum(dim=(1, 2))
+        seg_id = torch.from_numpy(ref_seg["seg_id"].astype(np.int64)).to(DEV)
+        n = ref_seg["n"]
+        a_ = torch.zeros(n, dtype=torch.float64, device=DEV).index_add_(0, seg_id, lhs)
+        b_ = torch.zeros(n, dtype=torch.float64, device=DEV).index_add_(0, seg_id, rhs)
+        scale_ = torch.zeros(n, dtype=torch.float64, device=DEV).index_add_(0, seg_id, lhs.abs() + rhs.abs()) + 1.0
+        assert float(((a_ - b_).abs() / scale_).max()) < 2e-2
+
+
+def test_padded_batch_equals_packed_at_real_tokens():
+    # the kernel-level form of "packing reaches the same loss as padding": real-token outputs agree
+    w = wl.make_workload(2, hq=4, hkv=4)
+    lay = wl.padded_layout(w.lengths, group=4)
+    pos_pad = np.concatenate([np.arange(p, dtype=np.int64) for _, p in lay])[None, :]
+    sr = np.cumsum([0] + [L for L, _ in lay])[:-1]
+    sp = np.cumsum([0] + [p for _, p in lay])[:-1]
+    ir = torch.from_numpy(np.concatenate([s + np.arange(L) for s, (L, _) in zip(sr, lay)])).to(DEV)
+    ip = torch.from_numpy(np.concatenate([s + np.arange(L) for s, (L, _) in zip(sp, lay)])).to(DEV)
+    q, k, v, do = (to_dev(a, "bf16") for a in (w.q, w.k, w.v, w.do))
+
+    def pad(t):
+        out = torch.zeros((pos_pad.shape[1],) + tuple(t.shape[1:]), dtype=t.dtype, device=DEV)
+        out[ip] = t[ir]
+        return out
+
+    seg = binding.pack_to_cu_seqlens(torch.from_numpy(w.position_ids).to(DEV))
+    o, lse = binding.varlen_attn_fwd(q, k, v, seg)
+    dq, dk, dv = binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, grad_dtype=torch.float32)
+    segp = binding.pack_to_cu_seqlens(torch.from_numpy(pos_pad).to(DEV))
+    qp, kp, vp, dop = pad(q), pad(k), pad(v), pad(do)
+    op, lsep = binding.varlen_attn_fwd(qp, kp, vp, segp)
+    dqp, dkp, dvp = binding.varlen_attn_bwd(dop, qp, kp, vp, op, lsep, segp, grad_dtype=torch.float32)
+    torch.cuda.synchronize()
+    # same arithmetic on a shifted tile grid: equal up to summation order
+    for a_, b_ in ((o, op), (dq, dqp), (dk, dkp), (dv, dvp)):
+        x, y = a_[ir].float(), b_[ip].float()
+        assert float((x - y).abs().max()) <= 2e-2
+        assert float((x - y).norm() / x.norm()) <= 5e-3
+    assert float((lse[:, ir] - lsep[:, ip]).abs().max()) <= 1e-3
