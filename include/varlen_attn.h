@@ -49,9 +49,8 @@ typedef enum {
 typedef enum { VA_F32 = 0, VA_BF16 = 1 } va_dtype;  /* element type of Q/K/V/O/dO and of the gradients */
 typedef enum { VA_I32 = 0, VA_I64 = 1 } va_itype;   /* element type of position_ids                     */
 
-/* Rows of Q (forward, dQ) or of K/V (dK/dV) handled by one workgroup; the
- * schedule below is expressed in tiles of this many consecutive tokens of a row. */
-#define VA_TILE 128
+/* The tile schedule is expressed in tiles of this many consecutive tokens of a packed row. */
+#define VA_TILE 256
 
 /*
  * Example boundaries and tile schedule of one packed stream.  A host struct of

@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libvarlen_attn.so")
 VA_OK = 0
 VA_F32, VA_BF16 = 0, 1
 VA_I32, VA_I64 = 0, 1
-VA_TILE = 128
+VA_TILE = 256
 STAGE_D, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 
 EXPORTS = (

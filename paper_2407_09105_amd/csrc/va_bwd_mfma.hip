@@ -21,6 +21,7 @@ namespace va {
 namespace {
 
 constexpr int kBT = 128;        // resident rows per workgroup (queries for dQ, keys for dK/dV)
+constexpr int kSub = VA_TILE / kBT;  // workgroup tiles per schedule tile
 constexpr int kBS = 64;         // streamed rows per LDS block
 constexpr int kRS = kD + 8;     // LDS stride of a row-major [64][128] block (elements)
 constexpr int kTS = kBS + 8;    // LDS stride of a transposed [128][64] block
@@ -42,12 +43,15 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  const int tile = q_tile_order[blockIdx.x / hq];
+  // schedule tiles hold kSub workgroup tiles; workgroups of one schedule tile are adjacent
+  const int tile = q_tile_order[blockIdx.x / (hq * kSub)];
+  const int sub = (blockIdx.x / hq) % kSub;
   const int h = blockIdx.x % hq;
   const int g = h / (hq / hkv);
   const int r = tile / tiles_per_row, m = tile % tiles_per_row;
   const int row_end = (r + 1) * T;
-  const int t0 = r * T + m * kBT;
+  const int t0 = r * T + m * VA_TILE + sub * kBT;
+  if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
   const int t_last = min(t0 + kBT, row_end) - 1;
 
   const int i_abs = t0 + wave * 32 + l32;
@@ -144,12 +148,14 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int l32 = lane & 31, half = lane >> 5;
-  const int tile = kv_tile_order[blockIdx.x / hkv];
+  const int tile = kv_tile_order[blockIdx.x / (hkv * kSub)];
+  const int sub = (blockIdx.x / hkv) % kSub;
   const int g = blockIdx.x % hkv;
   const int G = hq / hkv;
   const int r = tile / tiles_per_row, m = tile % tiles_per_row;
   const int row_end = (r + 1) * T;
-  const int t0 = r * T + m * kBT;
+  const int t0 = r * T + m * VA_TILE + sub * kBT;
+  if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
   const int t_last = min(t0 + kBT, row_end) - 1;
 
   const int j_abs = t0 + wave * 32 + l32;
@@ -253,8 +259,8 @@ hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const v
                            const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
                            va_dtype grad_dt, const va_segments &seg, int rows, int T, int hq,
                            int hkv, float scale, hipStream_t stream, unsigned stages) {
-  const int tiles_per_row = ceil_div(T, kBT);
-  const long long ntiles = (long long)rows * tiles_per_row;
+  const int tiles_per_row = ceil_div(T, VA_TILE);
+  const long long ntiles = (long long)rows * tiles_per_row * kSub;
   if (ntiles * hq > 0x7fffffffll) return hipErrorInvalidValue;
   const int N = rows * T;
   const float scale_log2 = scale * kLog2e;

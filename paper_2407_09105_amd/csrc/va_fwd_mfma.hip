@@ -5,11 +5,16 @@
 // the position-id scan (paper, Section 3); keys of other examples are never attended (Table 1)
 // and key blocks that lie wholly outside [seg_start[first row], last row] are never loaded.
 //
-// Shape of the computation: one workgroup (4 waves) per (128-token query tile, query head); wave
-// w owns query rows 32w..32w+31.  Key/value rows stream through LDS in blocks of 64.  Scores are
-// produced transposed, S^T = K Q^T, so a lane owns one query row (see va_mfma_common.h): the
-// online-softmax row maximum and sum are per-lane values plus one exchange with lane ^ 32, and
-// P^T leaves the accumulator registers directly as the B operand of O^T += V^T P^T.
+// Shape of the computation: one workgroup (4 waves) per (128-token query tile, query head), two
+// workgroups resident per CU so that one wave's softmax (vector ALU) overlaps another wave's
+// MFMAs on the same SIMD.  Wave w owns query rows 32w..32w+31.  Key/value rows stream through
+// LDS in blocks of 64, double-buffered; the next block travels HBM -> registers while the current
+// one is consumed.  Scores are produced transposed, S^T = K Q^T, so a lane owns one query row
+// (see va_mfma_common.h): the online-softmax row maximum and sum are per-lane values plus one
+// exchange with lane ^ 32, and P^T leaves the accumulator registers directly as the B operand
+// of O^T += V^T P^T.  V stays row-major in LDS; its transposed fragments come from the
+// transposing LDS read.  The running maximum is only moved (and O rescaled) when a row's
+// maximum grows by more than 2^kLazyLog2, which after the first block almost never happens.
 #include "va_internal.h"
 #include "va_mfma_common.h"
 
@@ -17,50 +22,55 @@ namespace va {
 namespace {
 
 constexpr int kBM = 128;          // query rows per workgroup
+constexpr int kSub = VA_TILE / kBM;
 constexpr int kBN = 64;           // key rows per LDS block
-constexpr int kKS = kD + 8;       // LDS row stride of the K block (elements): 272 B
-constexpr int kVS = kBN + 8;      // LDS row stride of the transposed V block: 144 B
-constexpr int kLdsK = kBN * kKS;  // elements
-constexpr int kLdsV = kD * kVS;
+constexpr int kKS = kD + 8;       // LDS row stride of a K block (elements): 272 B
+constexpr int kVS = kD + 32;      // LDS row stride of a V block: 320 B (conflict-free transposing reads)
+constexpr int kLdsK = kBN * kKS;  // elements per buffer
+constexpr int kLdsV = kBN * kVS;
+constexpr float kLazyLog2 = 8.f;  // keep a stale row maximum while probabilities stay <= 2^8
 
 __global__ void __launch_bounds__(256, 2)
 fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
                 const uint16_t *__restrict__ V, uint16_t *__restrict__ O, float *__restrict__ LSE,
                 const int32_t *__restrict__ seg_start, const int32_t *__restrict__ q_tile_order,
                 int N, int T, int tiles_per_row, int hq, int hkv, float scale_log2, float scale) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[kLdsK + kLdsV];
-  static_assert((kLdsK + kLdsV) * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit in the K/V buffers");
-  uint16_t *Ks = lds, *Vt = lds + kLdsK;
+  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * (kLdsK + kLdsV)];
+  static_assert(2 * (kLdsK + kLdsV) * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit in the K/V buffers");
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int l32 = lane & 31, half = lane >> 5;
+  const int tr_off = tr_lane_offset(lane, kVS);
 
-  // heavy tiles first; the heads of one tile are adjacent workgroups
-  const int tile = q_tile_order[blockIdx.x / hq];
+  // heavy schedule tiles first; the workgroups of one schedule tile (sub-tiles x heads) are adjacent
+  const int tile = uniform(q_tile_order[blockIdx.x / (hq * kSub)]);
+  const int sub = (blockIdx.x / hq) % kSub;
   const int h = blockIdx.x % hq;
   const int g = h / (hq / hkv);
   const int r = tile / tiles_per_row, m = tile % tiles_per_row;
-  const int row_end = (r + 1) * T;                     // one past the last token of this packed row
-  const int t0 = r * T + m * kBM;                      // first token of the tile
-  const int t_last = min(t0 + kBM, row_end) - 1;       // last valid token of the tile
+  const int row_end = (r + 1) * T;  // one past the last token of this packed row
+  const int t0 = r * T + m * VA_TILE + sub * kBM;
+  if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
+  const int t_last = min(t0 + kBM, row_end) - 1;
+  const int jb_lo = uniform(seg_start[t0]) / kBN, jb_hi = t_last / kBN;  // key blocks of this tile
 
-  // this lane's query row
-  const int i_abs = t0 + wave * 32 + l32;
-  const bool row_ok = i_abs <= t_last;
-  const int ss_i = row_ok ? seg_start[i_abs] : 0x7fffffff;
-  // this wave's row range (wave-uniform)
+  // this wave's rows (wave-uniform) and this lane's query row
   const int iw0 = t0 + wave * 32;
   const int iw1 = min(iw0 + 31, t_last);
   const bool wave_ok = iw0 <= t_last;
-  const int ss_min = wave_ok ? seg_start[iw0] : 0;
-  const int ss_max = wave_ok ? seg_start[iw1] : 0;
+  const bool wave_full = iw0 + 31 <= t_last;
+  const int ss_min = uniform(seg_start[min(iw0, t_last)]);
+  const int ss_max = uniform(seg_start[iw1 < iw0 ? t_last : iw1]);
+  const int i_abs = iw0 + l32;
+  const bool row_ok = i_abs <= t_last;
+  const int i_ld = min(i_abs, t_last);  // clamped: loads stay in bounds, results of dead rows are dropped
+  const int ss_i = row_ok ? seg_start[i_ld] : 0x7fffffff;
 
-  // Q fragment: B operand of S^T = K Q^T; 8 k-steps of 16
-  bf16x8 qf[8];
+  bf16x8 qf[8];  // B operands of S^T = K Q^T; 8 k-steps of 16
   {
-    const uint16_t *qp = Q + ((size_t)(row_ok ? i_abs : t0) * hq + h) * kD + half * 8;
+    const uint16_t *qp = Q + ((size_t)i_ld * hq + h) * kD + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(ldg16(qp + ks * 16, row_ok));
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(*(const u32x4 *)(qp + ks * 16));
   }
 
   f32x16 o_acc[4];
@@ -68,88 +78,108 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) o_acc[cb][v] = 0.f;
-  float m_run = -INFINITY;  // running row maximum (raw scores)
-  float l_run = 0.f;        // this lane's share of the running row sum
+  float m_ref = -INFINITY;  // reference maximum the stored probabilities are relative to (raw scores)
+  float l_run = 0.f;        // this lane's share of the running row sum, relative to m_ref
 
-  const int jb_lo = seg_start[t0] / kBN, jb_hi = t_last / kBN;
-  for (int jb = jb_lo; jb <= jb_hi; ++jb) {
-    const int j0 = jb * kBN;
-    __syncthreads();  // previous block fully consumed
-    load_rows_to_lds(K, j0, N, hkv, g, Ks, kKS);
-    load_rows_to_lds_transposed(V, j0, N, hkv, g, Vt, kVS);
+  // K/V block loads: buffer descriptors based at the workgroup's first key row
+  const size_t row_bytes = (size_t)hkv * kD * 2;
+  const size_t base_off = (size_t)jb_lo * kBN * row_bytes;
+  const size_t total = (size_t)N * row_bytes;
+  const buffer_t kbuf = make_buffer((const char *)K + base_off, total - base_off);
+  const buffer_t vbuf = make_buffer((const char *)V + base_off, total - base_off);
+  uint32_t ld_off[4];  // byte offset of this thread's 4 x 16 B inside a 64-row block
+  int st_k[4], st_v[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    const int q = threadIdx.x + 256 * p;
+    ld_off[p] = (uint32_t)((q >> 4) * row_bytes + g * kD * 2 + (q & 15) * 16);
+    st_k[p] = (q >> 4) * kKS + (q & 15) * 8;
+    st_v[p] = (q >> 4) * kVS + (q & 15) * 8;
+  }
+  const uint32_t blk_bytes = (uint32_t)(kBN * row_bytes);
+
+  u32x4 rk[4], rv[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) {
+    rk[p] = buffer_load16(kbuf, ld_off[p]);
+    rv[p] = buffer_load16(vbuf, ld_off[p]);
+  }
+
+  for (int jb = jb_lo; jb <= jb_hi; ++jb) {  // bounds are workgroup-uniform: barriers stay aligned
+    uint16_t *Kb = lds + ((jb - jb_lo) & 1) * (kLdsK + kLdsV);
+    uint16_t *Vb = Kb + kLdsK;
+    // block jb: registers -> LDS buffer (its previous content, block jb-2, was consumed before the
+    // barrier of iteration jb-1); then start fetching block jb+1
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      *(u32x4 *)(Kb + st_k[p]) = rk[p];
+      *(u32x4 *)(Vb + st_v[p]) = rv[p];
+    }
     __syncthreads();
-
+    if (jb < jb_hi) {
+      const uint32_t off = (uint32_t)(jb + 1 - jb_lo) * blk_bytes;
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        rk[p] = buffer_load16(kbuf, ld_off[p] + off);
+        rv[p] = buffer_load16(vbuf, ld_off[p] + off);
+      }
+    }
+    const int j0 = jb * kBN;
     if (!wave_ok || j0 > iw1 || j0 + kBN - 1 < ss_min) continue;  // wave-uniform
 
-    // ---- S^T = K Q^T for the two 32-key sub-blocks ----
-    f32x16 s[2];
-    bool sub_on[2];
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
       const int jl = j0 + sb * 32;
-      sub_on[sb] = !(jl > iw1 || jl + 31 < ss_min);
+      if (jl > iw1 || jl + 31 < ss_min) continue;  // wave-uniform: sub-block outside this wave's keys
+      // ---- S^T = K Q^T ----
+      f32x16 s;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s[sb][v] = 0.f;
-      if (sub_on[sb]) {
+      for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          bf16x8 kf = as_bf16x8(*(const u32x4 *)(Ks + (sb * 32 + l32) * kKS + ks * 16 + half * 8));
-          s[sb] = mfma32(kf, qf[ks], s[sb]);
-        }
-        const bool need_mask = !(jl >= ss_max && jl + 31 <= iw0);
-        if (need_mask) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int j = jl + acc_row(v, half);
-            if (j < ss_i || j > i_abs) s[sb][v] = -INFINITY;
-          }
-        }
-      } else {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[sb][v] = -INFINITY;
+      for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 kf = as_bf16x8(*(const u32x4 *)(Kb + (sb * 32 + l32) * kKS + ks * 16 + half * 8));
+        s = mfma32(kf, qf[ks], s);
       }
-    }
-
-    // ---- online softmax (lane owns a row; partner lane ^ 32 holds the other keys) ----
-    float mx = -INFINITY;
+      const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
+      if (!interior) {
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
+        for (int v = 0; v < 16; ++v) {
+          const int j = jl + acc_row(v, half);
+          if (j < ss_i || j > i_abs) s[v] = -INFINITY;
+        }
+      }
+      // ---- online softmax with a lazily moved reference maximum ----
+      float mx = fmaxf(s[0], s[1]);
 #pragma unroll
-      for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[sb][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_use) * scale_log2);
-    const float mneg = -m_use * scale_log2;
-    float psum = 0.f;
+      for (int v = 2; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[v]), s[v + 1]);
+      mx = pair_max(mx);
+      if (__any((mx - m_ref) * scale_log2 > kLazyLog2)) {  // rare after the first block
+        const float m_new = fmaxf(m_ref, mx);
+        const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * scale_log2);
+        l_run *= alpha;
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb)
+        for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) o_acc[cb][v] *= alpha;
+        m_ref = m_new;
+      }
+      // rows with nothing unmasked so far have m_ref = -inf: use 0 so that exp2(-inf - 0) = 0
+      const float mneg = (m_ref == -INFINITY) ? 0.f : -m_ref * scale_log2;
+      float psum = 0.f;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[sb][v], scale_log2, mneg));
-        s[sb][v] = p;
+        const float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, mneg));
+        s[v] = p;
         psum += p;
       }
-    l_run = l_run * alpha + psum;
-    m_run = m_new;
-    if (__any(alpha != 1.f)) {
-#pragma unroll
-      for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o_acc[cb][v] *= alpha;
-    }
-
-    // ---- O^T += V^T P^T ----
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      if (!sub_on[sb]) continue;
+      l_run += psum;
+      // ---- O^T += V^T P^T ----
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
-        const bf16x8 pf = pack_bf16x8(s[sb], 8 * s2);
-        const int kstep = sb * 2 + s2;
+        const bf16x8 pf = pack_bf16x8(s, 8 * s2);
 #pragma unroll
         for (int cb = 0; cb < 4; ++cb) {
-          bf16x8 vf = as_bf16x8(*(const u32x4 *)(Vt + (cb * 32 + l32) * kVS + kstep * 16 + half * 8));
+          const bf16x8 vf = lds_read_tr8(Vb + tr_off + (sb * 32 + s2 * 16) * kVS + cb * 32, 8 * kVS);
           o_acc[cb] = mfma32(vf, pf, o_acc[cb]);
         }
       }
@@ -157,10 +187,9 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   }
 
   // ---- epilogue: normalise, stage O through LDS, coalesced stores ----
-  const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+  const float l_tot = pair_sum(l_run);
   const float inv = row_ok ? 1.f / l_tot : 0.f;
-  if (row_ok && half == 0) LSE[(size_t)h * N + i_abs] = m_run * scale + __logf(l_tot);
-
+  if (row_ok && half == 0) LSE[(size_t)h * N + i_abs] = m_ref * scale + __logf(l_tot);
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
   store_transposed_tile<false>(o_acc, inv, stage, O, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h);
 }
@@ -170,8 +199,8 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
 hipError_t launch_mfma_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
                            const va_segments &seg, int rows, int T, int hq, int hkv, float scale,
                            hipStream_t stream) {
-  const int tiles_per_row = ceil_div(T, kBM);
-  const long long nwg = (long long)rows * tiles_per_row * hq;
+  const int tiles_per_row = ceil_div(T, VA_TILE);
+  const long long nwg = (long long)rows * tiles_per_row * kSub * hq;
   if (nwg <= 0 || nwg > 0x7fffffffll) return hipErrorInvalidValue;
   const float scale_log2 = scale * 1.4426950408889634f;
   fwd_mfma_kernel<<<(unsigned)nwg, 256, 0, stream>>>((const uint16_t *)Q, (const uint16_t *)K,

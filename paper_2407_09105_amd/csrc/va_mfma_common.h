@@ -56,6 +56,58 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
   return __builtin_bit_cast(uint32_t, r);
 }
 
+// Transposing LDS read (ds_read_b64_tr_b16).  Within each block of 16 lanes, lane 4r + q supplies
+// the address of 4 consecutive bf16 M[r][4q..4q+3] of a 4 x 16 matrix; lane i of the block receives
+// the column M[0..3][i].  With a row-major [rows][cols] LDS block this hands lane (c = lane % 32,
+// half = lane / 32) the elements X[j0 + 4 half + 0..3][c0 + c] -- four consecutive rows of one
+// column -- which is exactly what an A operand "rows = columns of X, k = rows of X" needs.
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+// Per-lane element offset into a row-major LDS block with `stride` elements per row: lane 4r + q of
+// 16-lane block b addresses row 4 (b / 2) + r, columns 16 (b % 2) + 4q.
+__device__ __forceinline__ int tr_lane_offset(int lane, int stride) {
+  const int b = lane >> 4, r = (lane & 15) >> 2, q = lane & 3;
+  return (4 * (b >> 1) + r) * stride + 16 * (b & 1) + 4 * q;
+}
+
+// A operand for one 16-row k-step whose B operand came from pack_bf16x8: rows {4 half + 0..3} and
+// {8 + 4 half + 0..3} of the block at `p` (already offset by tr_lane_offset); `second` = 8 rows.
+__device__ __forceinline__ bf16x8 lds_read_tr8(const uint16_t *p, int second) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
+  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + second));
+  const s16x8 r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// Wave-uniform value -> scalar register, so that conditions on it compile to scalar branches.
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// max / sum of a lane's value with that of lane ^ 32 (the lane holding the other keys of the
+// same row): v_permlane32_swap hands every lane both halves.
+__device__ __forceinline__ float pair_max(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r.x), __uint_as_float(r.y));
+}
+__device__ __forceinline__ float pair_sum(float x) {
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r.x) + __uint_as_float(r.y);
+}
+
+// Untyped buffer descriptor over `bytes` bytes at `base`: loads through it take a 32-bit byte
+// offset and return zero beyond the end, so block loads need no per-lane bounds branches.  The
+// whole offset goes into the per-lane (vector) operand: only that operand is range-checked, a
+// scalar offset is added after the check and can reach past the end of the tensor.
+typedef __amdgpu_buffer_rsrc_t buffer_t;
+__device__ __forceinline__ buffer_t make_buffer(const void *base, size_t bytes) {
+  const uint32_t n = bytes > 0xffffffffull ? 0xffffffffu : (uint32_t)bytes;
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)n, 0x00020000);
+}
+__device__ __forceinline__ u32x4 buffer_load16(buffer_t b, uint32_t byte_off) {
+  return __builtin_amdgcn_raw_buffer_load_b128(b, (int)byte_off, 0, 0);
+}
+
 // 16-byte global load with a validity guard (zero when !ok)
 __device__ __forceinline__ u32x4 ldg16(const uint16_t *p, bool ok) {
   u32x4 z = {0u, 0u, 0u, 0u};

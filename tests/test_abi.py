@@ -36,7 +36,7 @@ def test_plan_bytes(L):
     assert L.va_plan_bytes(0, 16) == 0 and L.va_plan_bytes(1, 0) == 0 and L.va_plan_bytes(-1, 4) == 0
     assert L.va_plan_bytes(65536, 65536) == 0          # N >= 2^31
     b = L.va_plan_bytes(1, 8192)
-    assert b >= 4 * (8193 + 3 * 8192 + 8 + 2 * 64) and b % 256 == 0
+    assert b >= 4 * (8193 + 3 * 8192 + 8 + 2 * 32) and b % 256 == 0
     assert L.va_plan_bytes(8, 8192) > b
 
 

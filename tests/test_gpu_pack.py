@@ -20,11 +20,12 @@ def _gpu_pack(pos_np, dtype=torch.int64):
 def _check_orders(got, pos_np):
     R, T = pos_np.shape
     ref = oracle.pack(pos_np)
-    tpr = (T + 127) // 128
+    TILE = binding.VA_TILE
+    tpr = (T + TILE - 1) // TILE
     nt = R * tpr
     tiles = np.arange(nt)
-    t0 = (tiles // tpr) * T + (tiles % tpr) * 128
-    t1 = np.minimum(t0 + 128, (tiles // tpr + 1) * T) - 1
+    t0 = (tiles // tpr) * T + (tiles % tpr) * TILE
+    t1 = np.minimum(t0 + TILE, (tiles // tpr + 1) * T) - 1
     cost_q = (t1 >> 6) - (ref["seg_start"][t0] >> 6) + 1
     cost_kv = ((ref["seg_end"][t1] - 1) >> 6) - (t0 >> 6) + 1
     for name, cost in (("q_tile_order", cost_q), ("kv_tile_order", cost_kv)):
