@@ -20,14 +20,13 @@
 namespace va {
 namespace {
 
-constexpr int kBT = 128;        // resident rows per workgroup (queries for dQ, keys for dK/dV)
+constexpr int kBT = 128;             // resident rows per workgroup (queries for dQ, keys for dK/dV)
 constexpr int kSub = VA_TILE / kBT;  // workgroup tiles per schedule tile
-constexpr int kBS = 64;         // streamed rows per LDS block
-constexpr int kRS = kD + 8;     // LDS stride of a row-major [64][128] block (elements)
-constexpr int kTS = kBS + 8;    // LDS stride of a transposed [128][64] block
-constexpr int kRowBlk = kBS * kRS;
-constexpr int kTrBlk = kD * kTS;
+constexpr int kBS = 64;              // streamed rows per LDS block
+constexpr int kBlk = kBS * kD;       // elements of one swizzled [64][128] LDS block (16 KB)
 constexpr float kLog2e = 1.4426950408889634f;
+
+typedef BlockCopy<kBS, 256> Copy;  // 4 x 16 B per thread and block
 
 // ---------------------------------------------------------------------------------------------
 template <bool kF32Out>
@@ -37,14 +36,14 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
                const float *__restrict__ LSE, const float *__restrict__ delta, void *__restrict__ dQ,
                const int32_t *__restrict__ seg_start, const int32_t *__restrict__ q_tile_order, int N,
                int T, int tiles_per_row, int hq, int hkv, float scale_log2, float scale) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kRowBlk + kTrBlk];
-  static_assert((2 * kRowBlk + kTrBlk) * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit");
-  uint16_t *Ks = lds, *Vs = lds + kRowBlk, *Kt = lds + 2 * kRowBlk;
+  // two stages of {K block, V block}, swizzled
+  __shared__ __attribute__((aligned(16))) uint16_t lds[4 * kBlk];
+  static_assert(4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit");
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int l32 = lane & 31, half = lane >> 5;
   // schedule tiles hold kSub workgroup tiles; workgroups of one schedule tile are adjacent
-  const int tile = q_tile_order[blockIdx.x / (hq * kSub)];
+  const int tile = uniform(q_tile_order[blockIdx.x / (hq * kSub)]);
   const int sub = (blockIdx.x / hq) % kSub;
   const int h = blockIdx.x % hq;
   const int g = h / (hq / hkv);
@@ -53,27 +52,30 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   const int t0 = r * T + m * VA_TILE + sub * kBT;
   if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
   const int t_last = min(t0 + kBT, row_end) - 1;
+  const int jb_lo = uniform(seg_start[t0]) / kBS, jb_hi = t_last / kBS;
 
-  const int i_abs = t0 + wave * 32 + l32;
-  const bool row_ok = i_abs <= t_last;
-  const int ss_i = row_ok ? seg_start[i_abs] : 0x7fffffff;
   const int iw0 = t0 + wave * 32;
   const int iw1 = min(iw0 + 31, t_last);
   const bool wave_ok = iw0 <= t_last;
-  const int ss_min = wave_ok ? seg_start[iw0] : 0;
-  const int ss_max = wave_ok ? seg_start[iw1] : 0;
+  const bool wave_full = iw0 + 31 <= t_last;
+  const int ss_min = uniform(seg_start[min(iw0, t_last)]);
+  const int ss_max = uniform(seg_start[iw1 < iw0 ? t_last : iw1]);
+  const int i_abs = iw0 + l32;
+  const bool row_ok = i_abs <= t_last;
+  const int i_ld = min(i_abs, t_last);  // clamped: loads stay in bounds, results of dead rows are dropped
+  const int ss_i = row_ok ? seg_start[i_ld] : 0x7fffffff;
 
   bf16x8 qf[8], gf[8];  // Q and dO rows of this lane: B operands
   {
-    const size_t off = ((size_t)(row_ok ? i_abs : t0) * hq + h) * kD + half * 8;
+    const size_t off = ((size_t)i_ld * hq + h) * kD + half * 8;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      qf[ks] = as_bf16x8(ldg16(Q + off + ks * 16, row_ok));
-      gf[ks] = as_bf16x8(ldg16(dO + off + ks * 16, row_ok));
+      qf[ks] = as_bf16x8(*(const u32x4 *)(Q + off + ks * 16));
+      gf[ks] = as_bf16x8(*(const u32x4 *)(dO + off + ks * 16));
     }
   }
-  const float lse2 = row_ok ? LSE[(size_t)h * N + i_abs] * kLog2e : 0.f;
-  const float dl = row_ok ? delta[(size_t)h * N + i_abs] : 0.f;
+  const float lse2 = LSE[(size_t)h * N + i_ld] * kLog2e;
+  const float dl = delta[(size_t)h * N + i_ld];
 
   f32x16 acc[4];
 #pragma unroll
@@ -81,15 +83,48 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[cb][v] = 0.f;
 
-  const int jb_lo = seg_start[t0] / kBS, jb_hi = t_last / kBS;
-  for (int jb = jb_lo; jb <= jb_hi; ++jb) {
+  const uint32_t row_lane = swz_row_lane_off(lane);
+  uint32_t tr_lane[2];
+  swz_tr_lane_off(lane, tr_lane);
+
+  const size_t row_bytes = (size_t)hkv * kD * 2;
+  const size_t base_off = (size_t)jb_lo * kBS * row_bytes;
+  const size_t total = (size_t)N * row_bytes;
+  const buffer_t kbuf = make_buffer((const char *)K + base_off, total - base_off);
+  const buffer_t vbuf = make_buffer((const char *)V + base_off, total - base_off);
+  uint32_t ld_off[Copy::kPer], st_off[Copy::kPer];
+#pragma unroll
+  for (int p = 0; p < Copy::kPer; ++p) {
+    ld_off[p] = Copy::global_off(p, row_bytes, g);
+    st_off[p] = Copy::lds_off(p);
+  }
+  const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
+  u32x4 rk[Copy::kPer], rv[Copy::kPer];
+#pragma unroll
+  for (int p = 0; p < Copy::kPer; ++p) {
+    rk[p] = buffer_load16(kbuf, ld_off[p]);
+    rv[p] = buffer_load16(vbuf, ld_off[p]);
+  }
+
+  for (int jb = jb_lo; jb <= jb_hi; ++jb) {  // bounds are workgroup-uniform: barriers stay aligned
+    uint16_t *Kb = lds + ((jb - jb_lo) & 1) * 2 * kBlk;
+    uint16_t *Vb = Kb + kBlk;
+#pragma unroll
+    for (int p = 0; p < Copy::kPer; ++p) {
+      *(u32x4 *)((char *)Kb + st_off[p]) = rk[p];
+      *(u32x4 *)((char *)Vb + st_off[p]) = rv[p];
+    }
+    __syncthreads();
+    if (jb < jb_hi) {
+      const uint32_t off = (uint32_t)(jb + 1 - jb_lo) * blk_bytes;
+#pragma unroll
+      for (int p = 0; p < Copy::kPer; ++p) {
+        rk[p] = buffer_load16(kbuf, ld_off[p] + off);
+        rv[p] = buffer_load16(vbuf, ld_off[p] + off);
+      }
+    }
     const int j0 = jb * kBS;
-    __syncthreads();
-    load_rows_to_lds(K, j0, N, hkv, g, Ks, kRS);
-    load_rows_to_lds(V, j0, N, hkv, g, Vs, kRS);
-    load_rows_to_lds_transposed(K, j0, N, hkv, g, Kt, kTS);
-    __syncthreads();
-    if (!wave_ok || j0 > iw1 || j0 + kBS - 1 < ss_min) continue;
+    if (!wave_ok || j0 > iw1 || j0 + kBS - 1 < ss_min) continue;  // wave-uniform
 
 #pragma unroll
     for (int sb = 0; sb < 2; ++sb) {
@@ -100,15 +135,14 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
       for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
       for (int ks = 0; ks < 8; ++ks) {
-        const int o = (sb * 32 + l32) * kRS + ks * 16 + half * 8;
-        s = mfma32(as_bf16x8(*(const u32x4 *)(Ks + o)), qf[ks], s);
-        dp = mfma32(as_bf16x8(*(const u32x4 *)(Vs + o)), gf[ks], dp);
+        s = mfma32(swz_read_row(Kb, row_lane, ks, sb * 32), qf[ks], s);     // S^T  = K Q^T
+        dp = mfma32(swz_read_row(Vb, row_lane, ks, sb * 32), gf[ks], dp);   // dP^T = V dO^T
       }
-      const bool need_mask = !(jl >= ss_max && jl + 31 <= iw0);
+      const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -lse2));
-        if (need_mask) {
+        if (!interior) {
           const int j = jl + acc_row(v, half);
           if (j < ss_i || j > i_abs) p = 0.f;
         }
@@ -117,12 +151,9 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 #pragma unroll
       for (int s2 = 0; s2 < 2; ++s2) {
         const bf16x8 df = pack_bf16x8(s, 8 * s2);
-        const int kstep = sb * 2 + s2;
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb) {
-          bf16x8 kf = as_bf16x8(*(const u32x4 *)(Kt + (cb * 32 + l32) * kTS + kstep * 16 + half * 8));
-          acc[cb] = mfma32(kf, df, acc[cb]);
-        }
+        for (int cb = 0; cb < 4; ++cb)  // dQ^T += K^T dS^T
+          acc[cb] = mfma32(swz_read_tr(Kb, tr_lane, cb, sb * 32 + s2 * 16), df, acc[cb]);
       }
     }
   }
@@ -140,15 +171,14 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
                  void *__restrict__ dV, const int32_t *__restrict__ seg_end,
                  const int32_t *__restrict__ kv_tile_order, int N, int T, int tiles_per_row, int hq,
                  int hkv, float scale_log2, float scale) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kRowBlk + 2 * kTrBlk + 4 * kBS];
-  static_assert((2 * kRowBlk + 2 * kTrBlk) * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit");
-  uint16_t *Qs = lds, *Gs = lds + kRowBlk, *Qt = lds + 2 * kRowBlk, *Gt = Qt + kTrBlk;
-  float *lse_s = (float *)(Gt + kTrBlk);  // [64] LSE * log2(e)
-  float *dl_s = lse_s + kBS;              // [64] D
+  // two stages of {Q block, dO block (swizzled), LSE * log2(e) [64], D [64]}
+  constexpr int kStage = 2 * kBlk + 4 * kBS;  // elements (floats take two)
+  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kStage];
+  static_assert(2 * kStage * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit");
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int l32 = lane & 31, half = lane >> 5;
-  const int tile = kv_tile_order[blockIdx.x / (hkv * kSub)];
+  const int tile = uniform(kv_tile_order[blockIdx.x / (hkv * kSub)]);
   const int sub = (blockIdx.x / hkv) % kSub;
   const int g = blockIdx.x % hkv;
   const int G = hq / hkv;
@@ -157,23 +187,29 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const int t0 = r * T + m * VA_TILE + sub * kBT;
   if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
   const int t_last = min(t0 + kBT, row_end) - 1;
+  // query blocks that can see a key of this tile: from the tile's first key to the end of the
+  // example holding its last key
+  const int ib_lo = t0 / kBS, ib_hi = (uniform(seg_end[t_last]) - 1) / kBS;
+  const int nb = ib_hi - ib_lo + 1;
 
-  const int j_abs = t0 + wave * 32 + l32;
-  const bool row_ok = j_abs <= t_last;
-  const int se_j = row_ok ? seg_end[j_abs] : 0;  // queries j_abs <= i < se_j see key j_abs
   const int jw0 = t0 + wave * 32;
   const int jw1 = min(jw0 + 31, t_last);
   const bool wave_ok = jw0 <= t_last;
-  const int se_min = wave_ok ? seg_end[jw0] : 0;
-  const int se_max = wave_ok ? seg_end[jw1] : 0;
+  const bool wave_full = jw0 + 31 <= t_last;
+  const int se_min = uniform(seg_end[min(jw0, t_last)]);
+  const int se_max = uniform(seg_end[jw1 < jw0 ? t_last : jw1]);
+  const int j_abs = jw0 + l32;
+  const bool row_ok = j_abs <= t_last;
+  const int j_ld = min(j_abs, t_last);
+  const int se_j = row_ok ? seg_end[j_ld] : 0;  // queries j_abs <= i < se_j see key j_abs
 
   bf16x8 kf[8], vf[8];  // K and V rows of this lane: B operands
   {
-    const size_t off = ((size_t)(row_ok ? j_abs : t0) * hkv + g) * kD + half * 8;
+    const size_t off = ((size_t)j_ld * hkv + g) * kD + half * 8;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-      kf[ks] = as_bf16x8(ldg16(K + off + ks * 16, row_ok));
-      vf[ks] = as_bf16x8(ldg16(V + off + ks * 16, row_ok));
+      kf[ks] = as_bf16x8(*(const u32x4 *)(K + off + ks * 16));
+      vf[ks] = as_bf16x8(*(const u32x4 *)(V + off + ks * 16));
     }
   }
 
@@ -183,65 +219,95 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 #pragma unroll
     for (int v = 0; v < 16; ++v) { dk_acc[cb][v] = 0.f; dv_acc[cb][v] = 0.f; }
 
-  const int ib_lo = t0 / kBS, ib_hi = (seg_end[t_last] - 1) / kBS;
-  for (int hh = 0; hh < G; ++hh) {
-    const int h = g * G + hh;
-    for (int ib = ib_lo; ib <= ib_hi; ++ib) {
-      const int i0 = ib * kBS;
-      __syncthreads();
-      load_rows_to_lds(Q, i0, N, hq, h, Qs, kRS);
-      load_rows_to_lds(dO, i0, N, hq, h, Gs, kRS);
-      load_rows_to_lds_transposed(Q, i0, N, hq, h, Qt, kTS);
-      load_rows_to_lds_transposed(dO, i0, N, hq, h, Gt, kTS);
-      if (threadIdx.x < kBS) {
-        const int i = i0 + threadIdx.x;
-        lse_s[threadIdx.x] = i < N ? LSE[(size_t)h * N + i] * kLog2e : 0.f;
-        dl_s[threadIdx.x] = i < N ? delta[(size_t)h * N + i] : 0.f;
-      }
-      __syncthreads();
-      if (!wave_ok || i0 + kBS - 1 < jw0 || i0 >= se_max) continue;
+  const uint32_t row_lane = swz_row_lane_off(lane);
+  uint32_t tr_lane[2];
+  swz_tr_lane_off(lane, tr_lane);
+
+  const size_t row_bytes = (size_t)hq * kD * 2;
+  const size_t base_off = (size_t)ib_lo * kBS * row_bytes;
+  const size_t total = (size_t)N * row_bytes;
+  const buffer_t qbuf = make_buffer((const char *)Q + base_off, total - base_off);
+  const buffer_t gbuf = make_buffer((const char *)dO + base_off, total - base_off);
+  uint32_t ld_off[Copy::kPer], st_off[Copy::kPer];
+#pragma unroll
+  for (int p = 0; p < Copy::kPer; ++p) {
+    ld_off[p] = Copy::global_off(p, row_bytes, 0);
+    st_off[p] = Copy::lds_off(p);
+  }
+  const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
+  u32x4 rq[Copy::kPer], rg[Copy::kPer];
+  float rstat = 0.f;  // threads 0..63: LSE * log2(e) of row tid; threads 64..127: D of row tid - 64
+  // iteration `it` streams query block ib_lo + it % nb of query head g * G + it / nb
+  auto fetch = [&](int it) {
+    const int hh = it / nb, ib = ib_lo + it % nb;
+    const uint32_t off = (uint32_t)(ib - ib_lo) * blk_bytes + (uint32_t)((g * G + hh) * kD * 2);
+#pragma unroll
+    for (int p = 0; p < Copy::kPer; ++p) {
+      rq[p] = buffer_load16(qbuf, ld_off[p] + off);
+      rg[p] = buffer_load16(gbuf, ld_off[p] + off);
+    }
+    if (threadIdx.x < 2 * kBS) {
+      const int i = min(ib * kBS + (int)(threadIdx.x & (kBS - 1)), N - 1);
+      const size_t x = (size_t)(g * G + hh) * N + i;
+      rstat = threadIdx.x < kBS ? LSE[x] * kLog2e : delta[x];
+    }
+  };
+  const int n_it = nb * G;
+  fetch(0);
+
+  for (int it = 0; it < n_it; ++it) {  // bounds are workgroup-uniform: barriers stay aligned
+    uint16_t *Qs = lds + (it & 1) * kStage;
+    uint16_t *Gs = Qs + kBlk;
+    float *lse_s = (float *)(Gs + kBlk);  // [64] LSE * log2(e)
+    float *dl_s = lse_s + kBS;            // [64] D
+#pragma unroll
+    for (int p = 0; p < Copy::kPer; ++p) {
+      *(u32x4 *)((char *)Qs + st_off[p]) = rq[p];
+      *(u32x4 *)((char *)Gs + st_off[p]) = rg[p];
+    }
+    if (threadIdx.x < 2 * kBS) lse_s[threadIdx.x] = rstat;
+    __syncthreads();
+    if (it + 1 < n_it) fetch(it + 1);
+    const int i0 = (ib_lo + it % nb) * kBS;
+    if (!wave_ok || i0 + kBS - 1 < jw0 || i0 >= se_max) continue;  // wave-uniform
 
 #pragma unroll
-      for (int sb = 0; sb < 2; ++sb) {
-        const int il = i0 + sb * 32;
-        if (il + 31 < jw0 || il >= se_max) continue;  // wave-uniform
-        f32x16 s, dp;
+    for (int sb = 0; sb < 2; ++sb) {
+      const int il = i0 + sb * 32;
+      if (il + 31 < jw0 || il >= se_max) continue;  // wave-uniform
+      f32x16 s, dp;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+      for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          const int o = (sb * 32 + l32) * kRS + ks * 16 + half * 8;
-          s = mfma32(as_bf16x8(*(const u32x4 *)(Qs + o)), kf[ks], s);
-          dp = mfma32(as_bf16x8(*(const u32x4 *)(Gs + o)), vf[ks], dp);
-        }
-        const bool need_mask = !(il >= jw1 && il + 31 < se_min);
+      for (int ks = 0; ks < 8; ++ks) {
+        s = mfma32(swz_read_row(Qs, row_lane, ks, sb * 32), kf[ks], s);     // S  = Q K^T
+        dp = mfma32(swz_read_row(Gs, row_lane, ks, sb * 32), vf[ks], dp);   // dP = dO V^T
+      }
+      const bool interior = wave_full && il >= jw1 && il + 31 < se_min;
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const f32x4 l4 = *(const f32x4 *)(lse_s + sb * 32 + q4 * 8 + half * 4);
-          const f32x4 d4 = *(const f32x4 *)(dl_s + sb * 32 + q4 * 8 + half * 4);
+      for (int q4 = 0; q4 < 4; ++q4) {
+        const f32x4 l4 = *(const f32x4 *)(lse_s + sb * 32 + q4 * 8 + half * 4);
+        const f32x4 d4 = *(const f32x4 *)(dl_s + sb * 32 + q4 * 8 + half * 4);
 #pragma unroll
-          for (int b = 0; b < 4; ++b) {
-            const int v = q4 * 4 + b;
-            float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -l4[b]));
-            if (need_mask) {
-              const int i = il + acc_row(v, half);
-              if (i < j_abs || i >= se_j) p = 0.f;
-            }
-            s[v] = p;                     // P
-            dp[v] = p * (dp[v] - d4[b]);  // dS
+        for (int b = 0; b < 4; ++b) {
+          const int v = q4 * 4 + b;
+          float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -l4[b]));
+          if (!interior) {
+            const int i = il + acc_row(v, half);
+            if (i < j_abs || i >= se_j) p = 0.f;
           }
+          s[v] = p;                     // P
+          dp[v] = p * (dp[v] - d4[b]);  // dS
         }
+      }
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8 pf = pack_bf16x8(s, 8 * s2);
-          const bf16x8 df = pack_bf16x8(dp, 8 * s2);
-          const int kstep = sb * 2 + s2;
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const bf16x8 pf = pack_bf16x8(s, 8 * s2);
+        const bf16x8 df = pack_bf16x8(dp, 8 * s2);
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb) {
-            const int o = (cb * 32 + l32) * kTS + kstep * 16 + half * 8;
-            dv_acc[cb] = mfma32(as_bf16x8(*(const u32x4 *)(Gt + o)), pf, dv_acc[cb]);
-            dk_acc[cb] = mfma32(as_bf16x8(*(const u32x4 *)(Qt + o)), df, dk_acc[cb]);
-          }
+        for (int cb = 0; cb < 4; ++cb) {
+          dv_acc[cb] = mfma32(swz_read_tr(Gs, tr_lane, cb, sb * 32 + s2 * 16), pf, dv_acc[cb]);  // dV^T += dO^T P
+          dk_acc[cb] = mfma32(swz_read_tr(Qs, tr_lane, cb, sb * 32 + s2 * 16), df, dk_acc[cb]);  // dK^T += Q^T dS
         }
       }
     }

@@ -108,6 +108,67 @@ __device__ __forceinline__ u32x4 buffer_load16(buffer_t b, uint32_t byte_off) {
   return __builtin_amdgcn_raw_buffer_load_b128(b, (int)byte_off, 0, 0);
 }
 
+// ---- swizzled LDS blocks --------------------------------------------------------------------
+// A [rows][128] bf16 block stored without padding (256 B per row, 16 chunks of 16 B); chunk ch of
+// row j sits at chunk position ch ^ swz(j).  With swz(j) = ((j & 3) << 2) | ((j >> 2) & 3) both
+// access patterns the backward needs are free of bank conflicts on the same copy of the data:
+//   - row reads (A operand "rows = block rows"): 16 consecutive rows, one chunk each, land on 16
+//     different chunk positions;
+//   - transposing reads (A operand "rows = block columns"): 4 consecutive rows x 4 chunks land on
+//     4 different groups of 4 chunk positions.
+__device__ __forceinline__ int swz(int j) { return ((j & 3) << 2) | ((j >> 2) & 3); }
+
+// Byte offset inside a swizzled block of this lane's row-read fragment for k-step 0 of the 32-row
+// group starting at row 0: row = lane % 32, chunk = half.  For k-step ks XOR the result with
+// (2 * ks) << 4; for the next 32-row group add 32 * 256.
+__device__ __forceinline__ uint32_t swz_row_lane_off(int lane) {
+  const int l32 = lane & 31, half = lane >> 5;
+  return (uint32_t)(l32 * 256 + ((half ^ swz(l32)) << 4));
+}
+__device__ __forceinline__ bf16x8 swz_read_row(const uint16_t *blk, uint32_t lane_off, int ks, int row0) {
+  const uint32_t off = (lane_off ^ (uint32_t)(ks << 5)) + (uint32_t)row0 * 256u;
+  return as_bf16x8(*(const u32x4 *)((const char *)blk + off));
+}
+
+// Transposing reads from a swizzled block: byte offsets of this lane's two 8-byte reads (rows
+// 4 half + r and 8 + 4 half + r of a 16-row k-step, column block 0).  For column block cb XOR with
+// cb << 6; for k-step base row j0 (a multiple of 16) add j0 * 256.
+__device__ __forceinline__ void swz_tr_lane_off(int lane, uint32_t (&off)[2]) {
+  const int b = lane >> 4, r = (lane & 15) >> 2, q = lane & 3;
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int j16 = 8 * t + 4 * (b >> 1) + r;
+    const int ch = 2 * (b & 1) + (q >> 1);
+    off[t] = (uint32_t)(j16 * 256 + ((ch ^ swz(j16)) << 4) + (q & 1) * 8);
+  }
+}
+__device__ __forceinline__ bf16x8 swz_read_tr(const uint16_t *blk, const uint32_t (&lane_off)[2], int cb, int j0) {
+  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
+  const char *base = (const char *)blk + (uint32_t)j0 * 256u;
+  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(base + (lane_off[0] ^ (uint32_t)(cb << 6))));
+  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(base + (lane_off[1] ^ (uint32_t)(cb << 6))));
+  const s16x8 r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(bf16x8, r);
+}
+
+// Cooperative block copy HBM -> registers -> swizzled LDS block for a workgroup of kThreads
+// threads: a [kRows][128] bf16 block is kRows * 16 chunks, kRows * 16 / kThreads per thread.
+template <int kRows, int kThreads>
+struct BlockCopy {
+  static constexpr int kPer = kRows * 16 / kThreads;
+  u32x4 r[kPer];
+  // byte offset (inside the block, head included) of chunk p of this thread in global memory
+  __device__ __forceinline__ static uint32_t global_off(int p, size_t row_bytes, int head) {
+    const int q = threadIdx.x + kThreads * p;
+    return (uint32_t)((q >> 4) * row_bytes + (size_t)head * kD * 2 + (q & 15) * 16);
+  }
+  __device__ __forceinline__ static uint32_t lds_off(int p) {
+    const int q = threadIdx.x + kThreads * p;
+    const int j = q >> 4, ch = q & 15;
+    return (uint32_t)(j * 256 + ((ch ^ swz(j)) << 4));
+  }
+};
+
 // 16-byte global load with a validity guard (zero when !ok)
 __device__ __forceinline__ u32x4 ldg16(const uint16_t *p, bool ok) {
   u32x4 z = {0u, 0u, 0u, 0u};
