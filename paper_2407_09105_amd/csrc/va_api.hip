@@ -52,6 +52,9 @@ va_status check_common(const va_segments *seg, int32_t rows, int32_t T, int32_t 
   if (hq % hkv != 0) return VA_ERR_SHAPE;
   if (dt != VA_F32 && dt != VA_BF16) return VA_ERR_UNSUPPORTED;
   if (d > 256) return VA_ERR_UNSUPPORTED;
+  if (hq > 65535) return VA_ERR_UNSUPPORTED;  // a grid dimension of the D kernel
+  // the MFMA kernels address one packed row's K/V (or Q/dO) through 32-bit byte offsets
+  if (dt == VA_BF16 && d == 128 && ((long long)T + 256) * hq * 256 >= (1ll << 32)) return VA_ERR_UNSUPPORTED;
   return VA_OK;
 }
 

@@ -162,6 +162,70 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   store_transposed_tile<kF32Out>(acc, scale, stage, dQ, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h);
 }
 
+// One 32-query sub-block of the dK/dV kernel for this wave's 32 keys.  All LDS fragments of a phase
+// are requested before the MFMAs that consume them, and the transposed fragments of the second
+// phase are requested before the exp / dS arithmetic, so LDS latency overlaps matrix and vector work.
+template <bool kMask>
+__device__ __forceinline__ void dkdv_subblock(f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4], const bf16x8 (&kf)[8],
+                                              const bf16x8 (&vf)[8], const uint16_t *Qs, const uint16_t *Gs,
+                                              const float *lse_s, const float *dl_s, int row0, uint32_t row_lane,
+                                              const uint32_t (&tr_lane)[2], int half, int il, int j_abs, int se_j,
+                                              float scale_log2) {
+  bf16x8 aq[8], ag[8];
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    aq[ks] = swz_read_row(Qs, row_lane, ks, row0);
+    ag[ks] = swz_read_row(Gs, row_lane, ks, row0);
+  }
+  f32x4 l4[4], d4[4];
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4) {
+    l4[q4] = *(const f32x4 *)(lse_s + row0 + q4 * 8 + half * 4);
+    d4[q4] = *(const f32x4 *)(dl_s + row0 + q4 * 8 + half * 4);
+  }
+  __builtin_amdgcn_sched_barrier(0);  // keep every read above in flight before the first MFMA
+  f32x16 s, dp;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+  for (int ks = 0; ks < 8; ++ks) {
+    s = mfma32(aq[ks], kf[ks], s);     // S  = Q K^T
+    dp = mfma32(ag[ks], vf[ks], dp);   // dP = dO V^T
+  }
+  bf16x8 tq[2][4], tg[2][4];
+#pragma unroll
+  for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+      tg[s2][cb] = swz_read_tr(Gs, tr_lane, cb, row0 + s2 * 16);
+      tq[s2][cb] = swz_read_tr(Qs, tr_lane, cb, row0 + s2 * 16);
+    }
+  __builtin_amdgcn_sched_barrier(0);  // transposed fragments land while the arithmetic below runs
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int v = q4 * 4 + b;
+      float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -l4[q4][b]));
+      if (kMask) {
+        const int i = il + acc_row(v, half);
+        if (i < j_abs || i >= se_j) p = 0.f;
+      }
+      s[v] = p;                         // P
+      dp[v] = p * (dp[v] - d4[q4][b]);  // dS
+    }
+#pragma unroll
+  for (int s2 = 0; s2 < 2; ++s2) {
+    const bf16x8 pf = pack_bf16x8(s, 8 * s2);
+    const bf16x8 df = pack_bf16x8(dp, 8 * s2);
+#pragma unroll
+    for (int cb = 0; cb < 4; ++cb) {
+      dv_acc[cb] = mfma32(tg[s2][cb], pf, dv_acc[cb]);  // dV^T += dO^T P
+      dk_acc[cb] = mfma32(tq[s2][cb], df, dk_acc[cb]);  // dK^T += Q^T dS
+    }
+  }
+}
+
 // ---------------------------------------------------------------------------------------------
 template <bool kF32Out>
 __global__ void __launch_bounds__(256, 1)
@@ -275,41 +339,13 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
     for (int sb = 0; sb < 2; ++sb) {
       const int il = i0 + sb * 32;
       if (il + 31 < jw0 || il >= se_max) continue;  // wave-uniform
-      f32x16 s, dp;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        s = mfma32(swz_read_row(Qs, row_lane, ks, sb * 32), kf[ks], s);     // S  = Q K^T
-        dp = mfma32(swz_read_row(Gs, row_lane, ks, sb * 32), vf[ks], dp);   // dP = dO V^T
-      }
       const bool interior = wave_full && il >= jw1 && il + 31 < se_min;
-#pragma unroll
-      for (int q4 = 0; q4 < 4; ++q4) {
-        const f32x4 l4 = *(const f32x4 *)(lse_s + sb * 32 + q4 * 8 + half * 4);
-        const f32x4 d4 = *(const f32x4 *)(dl_s + sb * 32 + q4 * 8 + half * 4);
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-          const int v = q4 * 4 + b;
-          float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -l4[b]));
-          if (!interior) {
-            const int i = il + acc_row(v, half);
-            if (i < j_abs || i >= se_j) p = 0.f;
-          }
-          s[v] = p;                     // P
-          dp[v] = p * (dp[v] - d4[b]);  // dS
-        }
-      }
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const bf16x8 pf = pack_bf16x8(s, 8 * s2);
-        const bf16x8 df = pack_bf16x8(dp, 8 * s2);
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb) {
-          dv_acc[cb] = mfma32(swz_read_tr(Gs, tr_lane, cb, sb * 32 + s2 * 16), pf, dv_acc[cb]);  // dV^T += dO^T P
-          dk_acc[cb] = mfma32(swz_read_tr(Qs, tr_lane, cb, sb * 32 + s2 * 16), df, dk_acc[cb]);  // dK^T += Q^T dS
-        }
-      }
+      if (interior)
+        dkdv_subblock<false>(dk_acc, dv_acc, kf, vf, Qs, Gs, lse_s, dl_s, sb * 32, row_lane, tr_lane, half, il,
+                             j_abs, se_j, scale_log2);
+      else
+        dkdv_subblock<true>(dk_acc, dv_acc, kf, vf, Qs, Gs, lse_s, dl_s, sb * 32, row_lane, tr_lane, half, il,
+                            j_abs, se_j, scale_log2);
     }
   }
 

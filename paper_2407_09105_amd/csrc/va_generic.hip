@@ -92,6 +92,31 @@ delta_kernel(const T *__restrict__ dO, const T *__restrict__ O, float *__restric
   if (lane == 0) delta[(size_t)h * N + i] = part;
 }
 
+// D for bf16, head_dim 128: 16 lanes per (token, head) row, 16 B of dO and of O per lane; a block
+// handles 64 consecutive tokens of one head, so the [Hq, N] result is written 64 B at a time.
+__global__ void __launch_bounds__(256)
+delta_bf16_d128_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ O,
+                       float *__restrict__ delta, int N, int hq) {
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+  const int h = blockIdx.y, c = threadIdx.x & 15, ti = threadIdx.x >> 4;
+#pragma unroll
+  for (int it = 0; it < 4; ++it) {
+    const int i = blockIdx.x * 64 + it * 16 + ti;
+    float part = 0.f;
+    if (i < N) {
+      const size_t x = ((size_t)i * hq + h) * 128 + c * 8;
+      const u32x4 a = *(const u32x4 *)(dO + x), b = *(const u32x4 *)(O + x);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        part += __uint_as_float(a[e] << 16) * __uint_as_float(b[e] << 16);
+        part += __uint_as_float(a[e] & 0xffff0000u) * __uint_as_float(b[e] & 0xffff0000u);
+      }
+    }
+    for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
+    if (c == 0 && i < N) delta[(size_t)h * N + i] = part;
+  }
+}
+
 // dQ: one wave per (i, h)
 template <typename T, typename TG>
 __global__ void __launch_bounds__(256)
@@ -210,6 +235,11 @@ hipError_t launch_generic_fwd(const void *Q, const void *K, const void *V, void 
 
 hipError_t launch_delta(const void *dO, const void *O, float *delta, int N, int hq, int d,
                         va_dtype dt, hipStream_t stream) {
+  if (dt == VA_BF16 && d == 128) {
+    delta_bf16_d128_kernel<<<dim3((unsigned)((N + 63) / 64), (unsigned)hq), 256, 0, stream>>>(
+        (const uint16_t *)dO, (const uint16_t *)O, delta, N, hq);
+    return hipGetLastError();
+  }
   const unsigned nb = blocks_for((long long)N * hq);
   if (dt == VA_F32)
     delta_kernel<float><<<nb, 256, 0, stream>>>((const float *)dO, (const float *)O, delta, N, hq, d);

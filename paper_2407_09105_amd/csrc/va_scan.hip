@@ -226,6 +226,133 @@ tile_rank_kernel(const int32_t *__restrict__ cost_q, const int32_t *__restrict__
   if (tile < ntiles) { order_q[rq] = tile; order_kv[rkv] = tile; }
 }
 
+// ---- one-workgroup path for short streams ------------------------------------------------------
+// Everything above in a single launch: 1024 threads scan up to kSmallMax tokens in passes of 8192
+// (8 consecutive tokens per thread), then compute tile costs and ranks.  Launch latency, not
+// bandwidth, bounds the scan at these sizes.
+constexpr int kSmallThreads = 1024;
+constexpr int kSmallPass = kSmallThreads * kPerThread;  // 8192 tokens
+constexpr int kSmallMaxPasses = 4;
+constexpr int kSmallMax = kSmallPass * kSmallMaxPasses;  // 32768 tokens
+constexpr int kSmallMaxTiles = kSmallMax / kTile * 8;    // rows may end in ragged tiles
+
+template <typename IdT>
+__global__ void __launch_bounds__(kSmallThreads)
+pack_small_kernel(const IdT *__restrict__ pos, int N, int T, int tiles_per_row, int ntiles,
+                  int32_t *__restrict__ cu, int32_t *__restrict__ seg_id, int32_t *__restrict__ seg_start,
+                  int32_t *__restrict__ seg_end, int32_t *__restrict__ meta,
+                  int32_t *__restrict__ order_q, int32_t *__restrict__ order_kv) {
+  constexpr int kWaves = kSmallThreads / 64;
+  __shared__ int s_cnt[kWaves], s_last[kWaves], s_first[kWaves];
+  __shared__ int p_cnt[kSmallMaxPasses], p_last[kSmallMaxPasses], p_first[kSmallMaxPasses];
+  __shared__ int s_longest[kWaves];
+  __shared__ int s_cq[kSmallMaxTiles], s_ckv[kSmallMaxTiles];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int npass = (N + kSmallPass - 1) / kSmallPass;
+
+  // pass aggregates
+  for (int ps = 0; ps < npass; ++ps) {
+    const int base = ps * kSmallPass + threadIdx.x * kPerThread;
+    int cnt = 0, last = -1, first = N;
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+      const int t = base + e;
+      if (t < N && is_start(pos, t, T)) { ++cnt; last = t; first = min(first, t); }
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      cnt += __shfl_xor(cnt, o, 64);
+      last = max(last, __shfl_xor(last, o, 64));
+      first = min(first, __shfl_xor(first, o, 64));
+    }
+    if (lane == 0) { s_cnt[w] = cnt; s_last[w] = last; s_first[w] = first; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      for (int i = 1; i < kWaves; ++i) { cnt += s_cnt[i]; last = max(last, s_last[i]); first = min(first, s_first[i]); }
+      p_cnt[ps] = cnt; p_last[ps] = last; p_first[ps] = first;
+    }
+    __syncthreads();
+  }
+
+  // final scan per pass with carries from the other passes
+  int longest = 0;
+  for (int ps = 0; ps < npass; ++ps) {
+    int c_cnt = 0, c_last = -1, c_first = N;
+    for (int i = 0; i < ps; ++i) { c_cnt += p_cnt[i]; c_last = max(c_last, p_last[i]); }
+    for (int i = npass - 1; i > ps; --i) c_first = min(c_first, p_first[i]);
+    const int base = ps * kSmallPass + threadIdx.x * kPerThread;
+    bool flag[kPerThread];
+    int cnt = 0, last = -1, first = N;
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+      const int t = base + e;
+      flag[e] = (t < N) && is_start(pos, t, T);
+      if (flag[e]) { ++cnt; last = t; first = min(first, t); }
+    }
+    const int icnt = wave_incl_add(cnt), ilast = wave_incl_max(last), sfirst = wave_suffix_min(first);
+    __syncthreads();  // previous pass finished with the wave arrays
+    if (lane == 63) { s_cnt[w] = icnt; s_last[w] = ilast; }
+    if (lane == 0) s_first[w] = sfirst;
+    __syncthreads();
+    int ecnt = __shfl_up(icnt, 1, 64), elast = __shfl_up(ilast, 1, 64), efirst = __shfl_down(sfirst, 1, 64);
+    if (lane == 0) { ecnt = 0; elast = -1; }
+    if (lane == 63) efirst = N;
+    for (int i = 0; i < w; ++i) { ecnt += s_cnt[i]; elast = max(elast, s_last[i]); }
+    for (int i = w + 1; i < kWaves; ++i) efirst = min(efirst, s_first[i]);
+    ecnt += c_cnt;
+    elast = max(elast, c_last);
+    efirst = min(efirst, c_first);
+    int nxt[kPerThread];
+    int run = efirst;
+#pragma unroll
+    for (int e = kPerThread - 1; e >= 0; --e) {
+      nxt[e] = run;
+      if (flag[e]) run = base + e;
+    }
+    int c = ecnt, l = elast;
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+      const int t = base + e;
+      if (t >= N) break;
+      if (flag[e]) { cu[c] = t; ++c; l = t; longest = max(longest, nxt[e] - t); }
+      seg_id[t] = c - 1;
+      seg_start[t] = l;
+      seg_end[t] = nxt[e];
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) longest = max(longest, __shfl_xor(longest, o, 64));
+  if (lane == 0) s_longest[w] = longest;
+  __syncthreads();  // also orders this workgroup's seg_start / seg_end stores before the loads below
+  if (threadIdx.x == 0) {
+    int n = 0;
+    for (int i = 0; i < npass; ++i) n += p_cnt[i];
+    for (int i = 1; i < kWaves; ++i) longest = max(longest, s_longest[i]);
+    meta[0] = n;
+    meta[1] = longest;
+    for (int i = 2; i < 8; ++i) meta[i] = 0;
+    cu[n] = N;
+  }
+
+  // tile costs and ranks (see tile_cost_kernel / tile_rank_kernel)
+  for (int tile = threadIdx.x; tile < ntiles; tile += kSmallThreads) {
+    const int r = tile / tiles_per_row, m = tile % tiles_per_row;
+    const int t0 = r * T + m * kTile;
+    const int t1 = min(t0 + kTile, (r + 1) * T) - 1;
+    s_cq[tile] = (t1 >> 6) - (seg_start[t0] >> 6) + 1;
+    s_ckv[tile] = ((seg_end[t1] - 1) >> 6) - (t0 >> 6) + 1;
+  }
+  __syncthreads();
+  for (int tile = threadIdx.x; tile < ntiles; tile += kSmallThreads) {
+    const int cq = s_cq[tile], ckv = s_ckv[tile];
+    int rq = 0, rkv = 0;
+    for (int o = 0; o < ntiles; ++o) {
+      rq += (s_cq[o] > cq) || (s_cq[o] == cq && o < tile);
+      rkv += (s_ckv[o] > ckv) || (s_ckv[o] == ckv && o < tile);
+    }
+    order_q[rq] = tile;
+    order_kv[rkv] = tile;
+  }
+}
+
 }  // namespace
 
 hipError_t launch_pack(const void *pos, va_itype it, int rows, int T, const va_segments &seg,
@@ -233,6 +360,17 @@ hipError_t launch_pack(const void *pos, va_itype it, int rows, int T, const va_s
   const int N = rows * T;
   const int nchunks = ceil_div(N, kScanChunk);
   const int tiles_per_row = ceil_div(T, kTile), ntiles = rows * tiles_per_row;
+  if (N <= kSmallMax && ntiles <= kSmallMaxTiles) {
+    if (it == VA_I64)
+      pack_small_kernel<int64_t><<<1, kSmallThreads, 0, stream>>>(
+          (const int64_t *)pos, N, T, tiles_per_row, ntiles, seg.cu_seqlens, seg.seg_id, seg.seg_start,
+          seg.seg_end, seg.meta, seg.q_tile_order, seg.kv_tile_order);
+    else
+      pack_small_kernel<int32_t><<<1, kSmallThreads, 0, stream>>>(
+          (const int32_t *)pos, N, T, tiles_per_row, ntiles, seg.cu_seqlens, seg.seg_id, seg.seg_start,
+          seg.seg_end, seg.meta, seg.q_tile_order, seg.kv_tile_order);
+    return hipGetLastError();
+  }
   int32_t *agg = seg.scratch;                  // [3 * nchunks]
   int32_t *carry = seg.scratch + 3 * nchunks;  // [3 * nchunks]
   int32_t *cost_q = carry + 3 * nchunks;       // [ntiles]
