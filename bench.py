@@ -182,6 +182,14 @@ def main():
     to_dev = lambda a: torch.from_numpy(a).cuda().to(torch.bfloat16)
     q, k, v, do = to_dev(w.q), to_dev(w.k), to_dev(w.v), to_dev(w.do)
 
+    # one plain device-to-device copy of known size (256 MiB read + 256 MiB written), outside every
+    # timed region: under `rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE` it calibrates the counters' units
+    calib_src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").fill_(1.0)
+    calib_dst = torch.empty_like(calib_src)
+    calib_dst.copy_(calib_src)
+    torch.cuda.synchronize()
+    del calib_src, calib_dst
+
     run = GpuRun(torch, binding, w.position_ids, q, k, v, do)
     ms, stages = timed(torch, run, args.steps, args.warmup)
     # the same K steps without stage events (the figure reported as `value`)

@@ -100,8 +100,9 @@ __device__ __forceinline__ float pair_sum(float x) {
 // whole offset goes into the per-lane (vector) operand: only that operand is range-checked, a
 // scalar offset is added after the check and can reach past the end of the tensor.
 typedef __amdgpu_buffer_rsrc_t buffer_t;
+constexpr uint32_t kPastEnd = 0xfffffff0u;  // an offset no buffer made by make_buffer contains
 __device__ __forceinline__ buffer_t make_buffer(const void *base, size_t bytes) {
-  const uint32_t n = bytes > 0xffffffffull ? 0xffffffffu : (uint32_t)bytes;
+  const uint32_t n = bytes > 0xffffff00ull ? 0xffffff00u : (uint32_t)bytes;
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, (int)n, 0x00020000);
 }
 __device__ __forceinline__ u32x4 buffer_load16(buffer_t b, uint32_t byte_off) {
