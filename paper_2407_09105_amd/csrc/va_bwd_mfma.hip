@@ -165,8 +165,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 // One 32-query sub-block of the dK/dV kernel for this wave's 32 keys.  All LDS fragments of a phase
 // are requested before the MFMAs that consume them, and the transposed fragments of the second
 // phase are requested before the exp / dS arithmetic, so LDS latency overlaps matrix and vector work.
-template <bool kMask>
-__device__ __forceinline__ void dkdv_subblock(f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4], const bf16x8 (&kf)[8],
+__device__ __forceinline__ void dkdv_subblock(bool need_mask, f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4], const bf16x8 (&kf)[8],
                                               const bf16x8 (&vf)[8], const uint16_t *Qs, const uint16_t *Gs,
                                               const float *lse_s, const float *dl_s, int row0, uint32_t row_lane,
                                               const uint32_t (&tr_lane)[2], int half, int il, int j_abs, int se_j,
@@ -206,13 +205,21 @@ __device__ __forceinline__ void dkdv_subblock(f32x16 (&dk_acc)[4], f32x16 (&dv_a
 #pragma unroll
     for (int b = 0; b < 4; ++b) {
       const int v = q4 * 4 + b;
-      float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -l4[q4][b]));
-      if (kMask) {
-        const int i = il + acc_row(v, half);
-        if (i < j_abs || i >= se_j) p = 0.f;
-      }
-      s[v] = p;                         // P
-      dp[v] = p * (dp[v] - d4[q4][b]);  // dS
+      s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -l4[q4][b]));  // P
+    }
+  if (need_mask) {  // wave-uniform; touches only the probabilities
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int i = il + acc_row(v, half);
+      if (i < j_abs || i >= se_j) s[v] = 0.f;
+    }
+  }
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4)
+#pragma unroll
+    for (int b = 0; b < 4; ++b) {
+      const int v = q4 * 4 + b;
+      dp[v] = s[v] * (dp[v] - d4[q4][b]);  // dS
     }
 #pragma unroll
   for (int s2 = 0; s2 < 2; ++s2) {
@@ -335,17 +342,13 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
     const int i0 = (ib_lo + it % nb) * kBS;
     if (!wave_ok || i0 + kBS - 1 < jw0 || i0 >= se_max) continue;  // wave-uniform
 
-#pragma unroll
+#pragma unroll 1  // one code instance: the accumulators keep their registers
     for (int sb = 0; sb < 2; ++sb) {
       const int il = i0 + sb * 32;
       if (il + 31 < jw0 || il >= se_max) continue;  // wave-uniform
       const bool interior = wave_full && il >= jw1 && il + 31 < se_min;
-      if (interior)
-        dkdv_subblock<false>(dk_acc, dv_acc, kf, vf, Qs, Gs, lse_s, dl_s, sb * 32, row_lane, tr_lane, half, il,
-                             j_abs, se_j, scale_log2);
-      else
-        dkdv_subblock<true>(dk_acc, dv_acc, kf, vf, Qs, Gs, lse_s, dl_s, sb * 32, row_lane, tr_lane, half, il,
-                            j_abs, se_j, scale_log2);
+      dkdv_subblock(!interior, dk_acc, dv_acc, kf, vf, Qs, Gs, lse_s, dl_s, sb * 32, row_lane, tr_lane, half, il,
+                    j_abs, se_j, scale_log2);
     }
   }
 
