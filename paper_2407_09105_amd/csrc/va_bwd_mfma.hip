@@ -306,42 +306,47 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
     st_off[p] = Copy::lds_off(p);
   }
   const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
-  u32x4 rq[Copy::kPer], rg[Copy::kPer];
-  float rstat = 0.f;  // threads 0..63: LSE * log2(e) of row tid; threads 64..127: D of row tid - 64
+  // Two register sets: the block of iteration `it` travels HBM -> registers during iterations
+  // it-2 and it-1.  Every request is issued unconditionally (a block past the end is requested at
+  // an offset outside the buffer and returns zeros without touching memory) so that the number of
+  // outstanding requests is the same on every path and a wait can target the older set only.
+  struct Regs { u32x4 q[Copy::kPer], g[Copy::kPer]; float stat; };
   // iteration `it` streams query block ib_lo + it % nb of query head g * G + it / nb
-  auto fetch = [&](int it) {
-    const int hh = it / nb, ib = ib_lo + it % nb;
+  const int n_it = nb * G;
+  const int stat_row = threadIdx.x & (kBS - 1);
+  const bool stat_is_lse = (threadIdx.x & kBS) == 0;  // threads 0..63 (and 128..191): LSE; others: D
+  const float *stat_src = stat_is_lse ? LSE : delta;
+  const float stat_mul = stat_is_lse ? kLog2e : 1.f;
+  auto fetch = [&](Regs &rr, int it) {
+    const bool live = it < n_it;
+    const int hh = live ? it / nb : 0, ib = live ? ib_lo + it % nb : ib_lo;
     const uint32_t off = (uint32_t)(ib - ib_lo) * blk_bytes + (uint32_t)((g * G + hh) * kD * 2);
 #pragma unroll
     for (int p = 0; p < Copy::kPer; ++p) {
-      rq[p] = buffer_load16(qbuf, ld_off[p] + off);
-      rg[p] = buffer_load16(gbuf, ld_off[p] + off);
+      const uint32_t o = live ? ld_off[p] + off : kPastEnd;
+      rr.q[p] = buffer_load16(qbuf, o);
+      rr.g[p] = buffer_load16(gbuf, o);
     }
-    if (threadIdx.x < 2 * kBS) {
-      const int i = min(ib * kBS + (int)(threadIdx.x & (kBS - 1)), N - 1);
-      const size_t x = (size_t)(g * G + hh) * N + i;
-      rstat = threadIdx.x < kBS ? LSE[x] * kLog2e : delta[x];
-    }
+    const int i = min(ib * kBS + stat_row, N - 1);
+    const size_t x = (size_t)(g * G + hh) * N + i;
+    rr.stat = stat_src[x];  // raw value; scaled when written to LDS (no use before the wait there)
   };
-  const int n_it = nb * G;
-  fetch(0);
-
-  for (int it = 0; it < n_it; ++it) {  // bounds are workgroup-uniform: barriers stay aligned
+  auto iteration = [&](int it, Regs &rr) {  // rr holds the block of iteration `it`
     uint16_t *Qs = lds + (it & 1) * kStage;
     uint16_t *Gs = Qs + kBlk;
     float *lse_s = (float *)(Gs + kBlk);  // [64] LSE * log2(e)
     float *dl_s = lse_s + kBS;            // [64] D
+    // its LDS stage held the block of iteration it-2, consumed before the barrier of iteration it-1
 #pragma unroll
     for (int p = 0; p < Copy::kPer; ++p) {
-      *(u32x4 *)((char *)Qs + st_off[p]) = rq[p];
-      *(u32x4 *)((char *)Gs + st_off[p]) = rg[p];
+      *(u32x4 *)((char *)Qs + st_off[p]) = rr.q[p];
+      *(u32x4 *)((char *)Gs + st_off[p]) = rr.g[p];
     }
-    if (threadIdx.x < 2 * kBS) lse_s[threadIdx.x] = rstat;
+    if (threadIdx.x < 2 * kBS) lse_s[threadIdx.x] = rr.stat * stat_mul;
     __syncthreads();
-    if (it + 1 < n_it) fetch(it + 1);
+    fetch(rr, it + 2);
     const int i0 = (ib_lo + it % nb) * kBS;
-    if (!wave_ok || i0 + kBS - 1 < jw0 || i0 >= se_max) continue;  // wave-uniform
-
+    if (!wave_ok || i0 + kBS - 1 < jw0 || i0 >= se_max) return;  // wave-uniform
 #pragma unroll 1  // one code instance: the accumulators keep their registers
     for (int sb = 0; sb < 2; ++sb) {
       const int il = i0 + sb * 32;
@@ -350,6 +355,13 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
       dkdv_subblock(!interior, dk_acc, dv_acc, kf, vf, Qs, Gs, lse_s, dl_s, sb * 32, row_lane, tr_lane, half, il,
                     j_abs, se_j, scale_log2);
     }
+  };
+  Regs r0, r1;
+  fetch(r0, 0);
+  fetch(r1, 1);
+  for (int it = 0; it < n_it; it += 2) {  // bounds are workgroup-uniform: barriers stay aligned
+    iteration(it, r0);
+    if (it + 1 < n_it) iteration(it + 1, r1);
   }
 
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
