@@ -246,7 +246,7 @@ def main():
         }
         del prun
     if not args.no_cpu_baseline:
-        heads = args.cpu_heads or {2: 16, 3: 8, 4: 16, 5: 0}.get(cfg_id, 8)
+        heads = args.cpu_heads or {2: 32, 3: 16, 4: 32, 5: 0}.get(cfg_id, 8)
         if heads:
             out["cpu_baseline"] = cpu_baseline(wl, cfg_id, heads)
         else:

@@ -28,7 +28,7 @@ bool plan_layout(int32_t rows, int32_t T, PlanLayout *L) {
   L->meta = off;      off += align_up(8 * 4);
   L->q_order = off;   off += align_up(ntiles * 4);
   L->kv_order = off;  off += align_up(ntiles * 4);
-  L->scratch = off;   off += align_up((6 * nchunks + 2 * ntiles) * 4);
+  L->scratch = off;   off += align_up((8 * nchunks + 4 * ntiles) * 4);
   L->total = off;
   return true;
 }

@@ -189,31 +189,41 @@ scan_finalize_kernel(const IdT *__restrict__ pos, int N, int T, const int32_t *_
 // Its keys run from seg_start[first token] to its last token: cost = number of 64-key blocks.
 // Key tile (same token range): its queries run from its first token to seg_end[last token]:
 // cost = number of 64-query blocks.  Every tile has cost >= 1 (the diagonal is never masked).
+//
+// Order: tiles are sorted by a key (longest governing example first, then that example's start,
+// then cost, heaviest first; ties by tile index).  The governing example is the one that fixes the
+// streamed range: the example of the first token for a query tile, of the last token for a key
+// tile.  Tiles of one long example thus run next to each other -- they stream the same K/V (or
+// Q/dO) blocks at about the same time and share them in L2 -- and long work still starts first.
+__device__ __forceinline__ unsigned long long tile_key(int len, int start, int cost) {
+  return ((unsigned long long)min(len, (1 << 20) - 1) << 43) |
+         ((unsigned long long)(0x7fffffff - start) << 12) | (unsigned long long)min(cost, 4095);
+}
 __global__ void __launch_bounds__(256)
 tile_cost_kernel(const int32_t *__restrict__ seg_start, const int32_t *__restrict__ seg_end, int T,
-                 int tiles_per_row, int ntiles, int32_t *__restrict__ cost_q,
-                 int32_t *__restrict__ cost_kv) {
+                 int tiles_per_row, int ntiles, unsigned long long *__restrict__ key_q,
+                 unsigned long long *__restrict__ key_kv) {
   const int tile = blockIdx.x * blockDim.x + threadIdx.x;
   if (tile >= ntiles) return;
   const int r = tile / tiles_per_row, m = tile % tiles_per_row;
   const int t0 = r * T + m * kTile;
   const int t1 = min(t0 + kTile, (r + 1) * T) - 1;  // last token of the tile
-  cost_q[tile] = (t1 >> 6) - (seg_start[t0] >> 6) + 1;
-  cost_kv[tile] = ((seg_end[t1] - 1) >> 6) - (t0 >> 6) + 1;
+  key_q[tile] = tile_key(seg_end[t0] - seg_start[t0], seg_start[t0], (t1 >> 6) - (seg_start[t0] >> 6) + 1);
+  key_kv[tile] = tile_key(seg_end[t1] - seg_start[t1], seg_start[t1], ((seg_end[t1] - 1) >> 6) - (t0 >> 6) + 1);
 }
 
-// order[rank] = tile, rank = number of tiles that are heavier (ties: lower index first)
+// order[rank] = tile, rank = number of tiles with a larger key (ties: lower index first)
 __global__ void __launch_bounds__(256)
-tile_rank_kernel(const int32_t *__restrict__ cost_q, const int32_t *__restrict__ cost_kv, int ntiles,
-                 int32_t *__restrict__ order_q, int32_t *__restrict__ order_kv) {
-  __shared__ int s_q[256], s_kv[256];
+tile_rank_kernel(const unsigned long long *__restrict__ cost_q, const unsigned long long *__restrict__ cost_kv,
+                 int ntiles, int32_t *__restrict__ order_q, int32_t *__restrict__ order_kv) {
+  __shared__ unsigned long long s_q[256], s_kv[256];
   const int tile = blockIdx.x * blockDim.x + threadIdx.x;
-  const int cq = tile < ntiles ? cost_q[tile] : 0, ckv = tile < ntiles ? cost_kv[tile] : 0;
+  const unsigned long long cq = tile < ntiles ? cost_q[tile] : 0, ckv = tile < ntiles ? cost_kv[tile] : 0;
   int rq = 0, rkv = 0;
   for (int b0 = 0; b0 < ntiles; b0 += 256) {
     const int o = b0 + threadIdx.x;
-    s_q[threadIdx.x] = o < ntiles ? cost_q[o] : -1;
-    s_kv[threadIdx.x] = o < ntiles ? cost_kv[o] : -1;
+    s_q[threadIdx.x] = o < ntiles ? cost_q[o] : 0;
+    s_kv[threadIdx.x] = o < ntiles ? cost_kv[o] : 0;
     __syncthreads();
     const int lim = min(256, ntiles - b0);
     for (int i = 0; i < lim; ++i) {
@@ -226,131 +236,143 @@ tile_rank_kernel(const int32_t *__restrict__ cost_q, const int32_t *__restrict__
   if (tile < ntiles) { order_q[rq] = tile; order_kv[rkv] = tile; }
 }
 
-// ---- one-workgroup path for short streams ------------------------------------------------------
-// Everything above in a single launch: 1024 threads scan up to kSmallMax tokens in passes of 8192
-// (8 consecutive tokens per thread), then compute tile costs and ranks.  Launch latency, not
-// bandwidth, bounds the scan at these sizes.
-constexpr int kSmallThreads = 1024;
-constexpr int kSmallPass = kSmallThreads * kPerThread;  // 8192 tokens
-constexpr int kSmallMaxPasses = 4;
-constexpr int kSmallMax = kSmallPass * kSmallMaxPasses;  // 32768 tokens
-constexpr int kSmallMaxTiles = kSmallMax / kTile * 8;    // rows may end in ragged tiles
+// ---- two-launch path for streams of up to kOnePassMaxChunks chunks --------------------------------
+// Launch 1: every chunk's workgroup derives its own carries by reading the ids of the chunks before
+// it (count and last start) and after it (first start) -- redundant reads that stay in L2, in
+// exchange for no inter-workgroup dependency and no separate carry kernel.  Launch 2: sort keys of
+// all tiles into LDS, ranks of this workgroup's tiles, and max_seqlen from the per-chunk maxima.
+constexpr int kOnePassMaxChunks = 4;  // 8192 tokens: beyond that the redundant reads cost more than two launches
+constexpr int kFusedMaxTiles = 2048;
 
 template <typename IdT>
-__global__ void __launch_bounds__(kSmallThreads)
-pack_small_kernel(const IdT *__restrict__ pos, int N, int T, int tiles_per_row, int ntiles,
-                  int32_t *__restrict__ cu, int32_t *__restrict__ seg_id, int32_t *__restrict__ seg_start,
-                  int32_t *__restrict__ seg_end, int32_t *__restrict__ meta,
-                  int32_t *__restrict__ order_q, int32_t *__restrict__ order_kv) {
-  constexpr int kWaves = kSmallThreads / 64;
-  __shared__ int s_cnt[kWaves], s_last[kWaves], s_first[kWaves];
-  __shared__ int p_cnt[kSmallMaxPasses], p_last[kSmallMaxPasses], p_first[kSmallMaxPasses];
-  __shared__ int s_longest[kWaves];
-  __shared__ int s_cq[kSmallMaxTiles], s_ckv[kSmallMaxTiles];
+__global__ void __launch_bounds__(kScanThreads)
+scan_onepass_kernel(const IdT *__restrict__ pos, int N, int T, int32_t *__restrict__ cu,
+                    int32_t *__restrict__ seg_id, int32_t *__restrict__ seg_start,
+                    int32_t *__restrict__ seg_end, int32_t *__restrict__ meta,
+                    int32_t *__restrict__ chunk_longest) {
+  __shared__ int s_cnt[kScanThreads / 64], s_last[kScanThreads / 64], s_first[kScanThreads / 64];
+  __shared__ int c_cnt, c_last, c_first;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int npass = (N + kSmallPass - 1) / kSmallPass;
-
-  // pass aggregates
-  for (int ps = 0; ps < npass; ++ps) {
-    const int base = ps * kSmallPass + threadIdx.x * kPerThread;
-    int cnt = 0, last = -1, first = N;
-#pragma unroll
-    for (int e = 0; e < kPerThread; ++e) {
-      const int t = base + e;
-      if (t < N && is_start(pos, t, T)) { ++cnt; last = t; first = min(first, t); }
-    }
+  const int chunk0 = blockIdx.x * kScanChunk;
+  // carries from the tokens before this chunk
+  {
+    int cnt = 0, last = -1;
+    for (int t = threadIdx.x; t < chunk0; t += kScanThreads)
+      if (is_start(pos, t, T)) { ++cnt; last = t; }
     for (int o = 32; o > 0; o >>= 1) {
       cnt += __shfl_xor(cnt, o, 64);
       last = max(last, __shfl_xor(last, o, 64));
-      first = min(first, __shfl_xor(first, o, 64));
     }
-    if (lane == 0) { s_cnt[w] = cnt; s_last[w] = last; s_first[w] = first; }
+    if (lane == 0) { s_cnt[w] = cnt; s_last[w] = last; }
     __syncthreads();
     if (threadIdx.x == 0) {
-      for (int i = 1; i < kWaves; ++i) { cnt += s_cnt[i]; last = max(last, s_last[i]); first = min(first, s_first[i]); }
-      p_cnt[ps] = cnt; p_last[ps] = last; p_first[ps] = first;
+      for (int i = 1; i < kScanThreads / 64; ++i) { cnt += s_cnt[i]; last = max(last, s_last[i]); }
+      c_cnt = cnt;
+      c_last = last;
     }
-    __syncthreads();
   }
-
-  // final scan per pass with carries from the other passes
-  int longest = 0;
-  for (int ps = 0; ps < npass; ++ps) {
-    int c_cnt = 0, c_last = -1, c_first = N;
-    for (int i = 0; i < ps; ++i) { c_cnt += p_cnt[i]; c_last = max(c_last, p_last[i]); }
-    for (int i = npass - 1; i > ps; --i) c_first = min(c_first, p_first[i]);
-    const int base = ps * kSmallPass + threadIdx.x * kPerThread;
-    bool flag[kPerThread];
-    int cnt = 0, last = -1, first = N;
-#pragma unroll
-    for (int e = 0; e < kPerThread; ++e) {
-      const int t = base + e;
-      flag[e] = (t < N) && is_start(pos, t, T);
-      if (flag[e]) { ++cnt; last = t; first = min(first, t); }
+  // first start after this chunk: look ahead one chunk at a time (the next row start bounds it)
+  {
+    int found = N;
+    for (int b0 = chunk0 + kScanChunk; b0 < N && found == N; b0 += kScanChunk) {
+      int first = N;
+      for (int t = b0 + threadIdx.x; t < min(b0 + kScanChunk, N); t += kScanThreads)
+        if (is_start(pos, t, T)) first = min(first, t);
+      for (int o = 32; o > 0; o >>= 1) first = min(first, __shfl_xor(first, o, 64));
+      __syncthreads();  // s_first free (previous round consumed)
+      if (lane == 0) s_first[w] = first;
+      __syncthreads();
+      for (int i = 0; i < kScanThreads / 64; ++i) found = min(found, s_first[i]);  // same value in every thread
     }
-    const int icnt = wave_incl_add(cnt), ilast = wave_incl_max(last), sfirst = wave_suffix_min(first);
-    __syncthreads();  // previous pass finished with the wave arrays
-    if (lane == 63) { s_cnt[w] = icnt; s_last[w] = ilast; }
-    if (lane == 0) s_first[w] = sfirst;
     __syncthreads();
-    int ecnt = __shfl_up(icnt, 1, 64), elast = __shfl_up(ilast, 1, 64), efirst = __shfl_down(sfirst, 1, 64);
-    if (lane == 0) { ecnt = 0; elast = -1; }
-    if (lane == 63) efirst = N;
-    for (int i = 0; i < w; ++i) { ecnt += s_cnt[i]; elast = max(elast, s_last[i]); }
-    for (int i = w + 1; i < kWaves; ++i) efirst = min(efirst, s_first[i]);
-    ecnt += c_cnt;
-    elast = max(elast, c_last);
-    efirst = min(efirst, c_first);
-    int nxt[kPerThread];
-    int run = efirst;
+    if (threadIdx.x == 0) c_first = found;
+  }
+  __syncthreads();
+  // local scan, as in scan_finalize_kernel
+  const int base = chunk0 + threadIdx.x * kPerThread;
+  bool flag[kPerThread];
+  int cnt = 0, last = -1, first = N;
 #pragma unroll
-    for (int e = kPerThread - 1; e >= 0; --e) {
-      nxt[e] = run;
-      if (flag[e]) run = base + e;
-    }
-    int c = ecnt, l = elast;
+  for (int e = 0; e < kPerThread; ++e) {
+    const int t = base + e;
+    flag[e] = (t < N) && is_start(pos, t, T);
+    if (flag[e]) { ++cnt; last = t; first = min(first, t); }
+  }
+  const int icnt = wave_incl_add(cnt), ilast = wave_incl_max(last), sfirst = wave_suffix_min(first);
+  if (lane == 63) { s_cnt[w] = icnt; s_last[w] = ilast; }
+  if (lane == 0) s_first[w] = sfirst;
+  __syncthreads();
+  int ecnt = __shfl_up(icnt, 1, 64), elast = __shfl_up(ilast, 1, 64), efirst = __shfl_down(sfirst, 1, 64);
+  if (lane == 0) { ecnt = 0; elast = -1; }
+  if (lane == 63) efirst = N;
+  for (int i = 0; i < w; ++i) { ecnt += s_cnt[i]; elast = max(elast, s_last[i]); }
+  for (int i = w + 1; i < kScanThreads / 64; ++i) efirst = min(efirst, s_first[i]);
+  ecnt += c_cnt;
+  elast = max(elast, c_last);
+  efirst = min(efirst, c_first);
+  int nxt[kPerThread];
+  int run = efirst;
 #pragma unroll
-    for (int e = 0; e < kPerThread; ++e) {
-      const int t = base + e;
-      if (t >= N) break;
-      if (flag[e]) { cu[c] = t; ++c; l = t; longest = max(longest, nxt[e] - t); }
-      seg_id[t] = c - 1;
-      seg_start[t] = l;
-      seg_end[t] = nxt[e];
-    }
+  for (int e = kPerThread - 1; e >= 0; --e) {
+    nxt[e] = run;
+    if (flag[e]) run = base + e;
+  }
+  int c = ecnt, l = elast, longest = 0;
+#pragma unroll
+  for (int e = 0; e < kPerThread; ++e) {
+    const int t = base + e;
+    if (t >= N) break;
+    if (flag[e]) { cu[c] = t; ++c; l = t; longest = max(longest, nxt[e] - t); }
+    seg_id[t] = c - 1;
+    seg_start[t] = l;
+    seg_end[t] = nxt[e];
   }
   for (int o = 32; o > 0; o >>= 1) longest = max(longest, __shfl_xor(longest, o, 64));
-  if (lane == 0) s_longest[w] = longest;
-  __syncthreads();  // also orders this workgroup's seg_start / seg_end stores before the loads below
-  if (threadIdx.x == 0) {
-    int n = 0;
-    for (int i = 0; i < npass; ++i) n += p_cnt[i];
-    for (int i = 1; i < kWaves; ++i) longest = max(longest, s_longest[i]);
-    meta[0] = n;
-    meta[1] = longest;
+  __syncthreads();  // s_cnt free
+  if (lane == 0) s_cnt[w] = longest;
+  // the last thread of the last chunk knows the total number of examples
+  if (blockIdx.x == gridDim.x - 1 && threadIdx.x == kScanThreads - 1) {
+    meta[0] = c;
     for (int i = 2; i < 8; ++i) meta[i] = 0;
-    cu[n] = N;
+    cu[c] = N;
   }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int i = 1; i < kScanThreads / 64; ++i) longest = max(longest, s_cnt[i]);
+    chunk_longest[blockIdx.x] = longest;
+  }
+}
 
-  // tile costs and ranks (see tile_cost_kernel / tile_rank_kernel)
-  for (int tile = threadIdx.x; tile < ntiles; tile += kSmallThreads) {
+__global__ void __launch_bounds__(256)
+tile_order_fused_kernel(const int32_t *__restrict__ seg_start, const int32_t *__restrict__ seg_end, int T,
+                        int tiles_per_row, int ntiles, const int32_t *__restrict__ chunk_longest, int nchunks,
+                        int32_t *__restrict__ meta, int32_t *__restrict__ order_q,
+                        int32_t *__restrict__ order_kv) {
+  __shared__ unsigned long long s_q[kFusedMaxTiles], s_kv[kFusedMaxTiles];
+  for (int tile = threadIdx.x; tile < ntiles; tile += 256) {
     const int r = tile / tiles_per_row, m = tile % tiles_per_row;
     const int t0 = r * T + m * kTile;
     const int t1 = min(t0 + kTile, (r + 1) * T) - 1;
-    s_cq[tile] = (t1 >> 6) - (seg_start[t0] >> 6) + 1;
-    s_ckv[tile] = ((seg_end[t1] - 1) >> 6) - (t0 >> 6) + 1;
+    const int ss0 = seg_start[t0], se0 = seg_end[t0], ss1 = seg_start[t1], se1 = seg_end[t1];
+    s_q[tile] = tile_key(se0 - ss0, ss0, (t1 >> 6) - (ss0 >> 6) + 1);
+    s_kv[tile] = tile_key(se1 - ss1, ss1, ((se1 - 1) >> 6) - (t0 >> 6) + 1);
+  }
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    int longest = 0;
+    for (int i = 0; i < nchunks; ++i) longest = max(longest, chunk_longest[i]);
+    meta[1] = longest;
   }
   __syncthreads();
-  for (int tile = threadIdx.x; tile < ntiles; tile += kSmallThreads) {
-    const int cq = s_cq[tile], ckv = s_ckv[tile];
-    int rq = 0, rkv = 0;
-    for (int o = 0; o < ntiles; ++o) {
-      rq += (s_cq[o] > cq) || (s_cq[o] == cq && o < tile);
-      rkv += (s_ckv[o] > ckv) || (s_ckv[o] == ckv && o < tile);
-    }
-    order_q[rq] = tile;
-    order_kv[rkv] = tile;
+  const int tile = blockIdx.x * 256 + threadIdx.x;
+  if (tile >= ntiles) return;
+  const unsigned long long cq = s_q[tile], ckv = s_kv[tile];
+  int rq = 0, rkv = 0;
+  for (int o = 0; o < ntiles; ++o) {
+    rq += (s_q[o] > cq) || (s_q[o] == cq && o < tile);
+    rkv += (s_kv[o] > ckv) || (s_kv[o] == ckv && o < tile);
   }
+  order_q[rq] = tile;
+  order_kv[rkv] = tile;
 }
 
 }  // namespace
@@ -360,21 +382,23 @@ hipError_t launch_pack(const void *pos, va_itype it, int rows, int T, const va_s
   const int N = rows * T;
   const int nchunks = ceil_div(N, kScanChunk);
   const int tiles_per_row = ceil_div(T, kTile), ntiles = rows * tiles_per_row;
-  if (N <= kSmallMax && ntiles <= kSmallMaxTiles) {
+  if (nchunks <= kOnePassMaxChunks && ntiles <= kFusedMaxTiles) {
+    int32_t *chunk_longest = seg.scratch;  // [nchunks]
     if (it == VA_I64)
-      pack_small_kernel<int64_t><<<1, kSmallThreads, 0, stream>>>(
-          (const int64_t *)pos, N, T, tiles_per_row, ntiles, seg.cu_seqlens, seg.seg_id, seg.seg_start,
-          seg.seg_end, seg.meta, seg.q_tile_order, seg.kv_tile_order);
+      scan_onepass_kernel<int64_t><<<nchunks, kScanThreads, 0, stream>>>(
+          (const int64_t *)pos, N, T, seg.cu_seqlens, seg.seg_id, seg.seg_start, seg.seg_end, seg.meta, chunk_longest);
     else
-      pack_small_kernel<int32_t><<<1, kSmallThreads, 0, stream>>>(
-          (const int32_t *)pos, N, T, tiles_per_row, ntiles, seg.cu_seqlens, seg.seg_id, seg.seg_start,
-          seg.seg_end, seg.meta, seg.q_tile_order, seg.kv_tile_order);
+      scan_onepass_kernel<int32_t><<<nchunks, kScanThreads, 0, stream>>>(
+          (const int32_t *)pos, N, T, seg.cu_seqlens, seg.seg_id, seg.seg_start, seg.seg_end, seg.meta, chunk_longest);
+    tile_order_fused_kernel<<<ceil_div(ntiles, 256), 256, 0, stream>>>(
+        seg.seg_start, seg.seg_end, T, tiles_per_row, ntiles, chunk_longest, nchunks, seg.meta, seg.q_tile_order,
+        seg.kv_tile_order);
     return hipGetLastError();
   }
   int32_t *agg = seg.scratch;                  // [3 * nchunks]
   int32_t *carry = seg.scratch + 3 * nchunks;  // [3 * nchunks]
-  int32_t *cost_q = carry + 3 * nchunks;       // [ntiles]
-  int32_t *cost_kv = cost_q + ntiles;          // [ntiles]
+  unsigned long long *cost_q = (unsigned long long *)(seg.scratch + 8 * nchunks);  // [ntiles] sort keys
+  unsigned long long *cost_kv = cost_q + ntiles;                                   // [ntiles]
   if (it == VA_I64)
     scan_aggregate_kernel<int64_t><<<nchunks, kScanThreads, 0, stream>>>((const int64_t *)pos, N, T, agg);
   else

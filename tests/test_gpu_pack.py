@@ -26,15 +26,21 @@ def _check_orders(got, pos_np):
     tiles = np.arange(nt)
     t0 = (tiles // tpr) * T + (tiles % tpr) * TILE
     t1 = np.minimum(t0 + TILE, (tiles // tpr + 1) * T) - 1
-    cost_q = (t1 >> 6) - (ref["seg_start"][t0] >> 6) + 1
-    cost_kv = ((ref["seg_end"][t1] - 1) >> 6) - (t0 >> 6) + 1
-    for name, cost in (("q_tile_order", cost_q), ("kv_tile_order", cost_kv)):
+    ss, se = ref["seg_start"].astype(np.int64), ref["seg_end"].astype(np.int64)
+    cost_q = (t1 >> 6) - (ss[t0] >> 6) + 1
+    cost_kv = ((se[t1] - 1) >> 6) - (t0 >> 6) + 1
+
+    def key(length, start, cost):
+        return (np.minimum(length, (1 << 20) - 1) << 43) | ((0x7FFFFFFF - start) << 12) | np.minimum(cost, 4095)
+
+    key_q = key(se[t0] - ss[t0], ss[t0], cost_q)       # governed by the example of the tile's first token
+    key_kv = key(se[t1] - ss[t1], ss[t1], cost_kv)     # ... of its last token
+    for name, k, cost in (("q_tile_order", key_q, cost_q), ("kv_tile_order", key_kv, cost_kv)):
         order = got[name]
         assert sorted(order.tolist()) == list(range(nt)), name     # a permutation of the tiles
-        c = cost[order]
-        assert np.all(c[:-1] >= c[1:]), name                       # heaviest first
-        # ties keep index order: the result is unique
-        expect = np.lexsort((tiles, -cost))
+        assert np.all(cost >= 1)
+        # largest key first, ties keep index order: the result is unique
+        expect = np.lexsort((tiles, -k))
         assert np.array_equal(order, expect), name
 
 
