@@ -43,9 +43,10 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int l32 = lane & 31, half = lane >> 5;
   // schedule tiles hold kSub workgroup tiles; workgroups of one schedule tile are adjacent
-  const int tile = uniform(q_tile_order[blockIdx.x / (hq * kSub)]);
-  const int sub = (blockIdx.x / hq) % kSub;
-  const int h = blockIdx.x % hq;
+  const int wg = xcd_group_remap(blockIdx.x, hq / hkv, gridDim.x);
+  const int tile = uniform(q_tile_order[wg / (hq * kSub)]);
+  const int sub = (wg / hq) % kSub;
+  const int h = wg % hq;
   const int g = h / (hq / hkv);
   const int r = tile / tiles_per_row, m = tile % tiles_per_row;
   const int row_end = (r + 1) * T;

@@ -43,9 +43,10 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   const int tr_off = tr_lane_offset(lane, kVS);
 
   // heavy schedule tiles first; the workgroups of one schedule tile (sub-tiles x heads) are adjacent
-  const int tile = uniform(q_tile_order[blockIdx.x / (hq * kSub)]);
-  const int sub = (blockIdx.x / hq) % kSub;
-  const int h = blockIdx.x % hq;
+  const int wg = xcd_group_remap(blockIdx.x, hq / hkv, gridDim.x);
+  const int tile = uniform(q_tile_order[wg / (hq * kSub)]);
+  const int sub = (wg / hq) % kSub;
+  const int h = wg % hq;
   const int g = h / (hq / hkv);
   const int r = tile / tiles_per_row, m = tile % tiles_per_row;
   const int row_end = (r + 1) * T;  // one past the last token of this packed row

@@ -81,6 +81,17 @@ __device__ __forceinline__ bf16x8 lds_read_tr8(const uint16_t *p, int second) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by workgroup id.  With
+// grouped-query attention the G query heads of one KV head stream the same K/V blocks; this maps
+// workgroup id -> logical index so that G consecutive logical indices (the heads of one group, which
+// are adjacent in the logical order) land on one XCD in consecutive slots, while the logical
+// (longest-first) order is otherwise preserved at a granularity of 8 G workgroups.
+__device__ __forceinline__ int xcd_group_remap(int wg, int G, int n_wg) {
+  if (G == 1 || n_wg % (8 * G) != 0) return wg;
+  const int xcd = wg & 7, slot = wg >> 3;
+  return ((slot / G) * 8 + xcd) * G + slot % G;
+}
+
 // Wave-uniform value -> scalar register, so that conditions on it compile to scalar branches.
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
