@@ -8,8 +8,11 @@
 // Shape of the computation: one workgroup (4 waves) per (128-token query tile, query head), two
 // workgroups resident per CU so that one wave's softmax (vector ALU) overlaps another wave's
 // MFMAs on the same SIMD.  Wave w owns query rows 32w..32w+31.  Key/value rows stream through
-// LDS in blocks of 64, double-buffered; the next block travels HBM -> registers while the current
-// one is consumed.  Scores are produced transposed, S^T = K Q^T, so a lane owns one query row
+// LDS in blocks of 64, double-buffered; the next block is copied HBM -> LDS by the load unit itself
+// (buffer loads with an LDS destination: no registers, no LDS store instructions) while the
+// current one is consumed.  Blocks are stored unpadded in the XOR-swizzled layout of
+// va_mfma_common.h; since such a load writes 64 consecutive 16-byte chunks, the swizzle is applied
+// on the global side (each lane fetches the chunk that belongs at its LDS position).  Scores are produced transposed, S^T = K Q^T, so a lane owns one query row
 // (see va_mfma_common.h): the online-softmax row maximum and sum are per-lane values plus one
 // exchange with lane ^ 32, and P^T leaves the accumulator registers directly as the B operand
 // of O^T += V^T P^T.  V stays row-major in LDS; its transposed fragments come from the
@@ -24,10 +27,7 @@ namespace {
 constexpr int kBM = 128;          // query rows per workgroup
 constexpr int kSub = VA_TILE / kBM;
 constexpr int kBN = 64;           // key rows per LDS block
-constexpr int kKS = kD + 8;       // LDS row stride of a K block (elements): 272 B
-constexpr int kVS = kD + 32;      // LDS row stride of a V block: 320 B (conflict-free transposing reads)
-constexpr int kLdsK = kBN * kKS;  // elements per buffer
-constexpr int kLdsV = kBN * kVS;
+constexpr int kBlk = kBN * kD;    // elements of one swizzled [64][128] LDS block (16 KB)
 constexpr float kLazyLog2 = 8.f;  // keep a stale row maximum while probabilities stay <= 2^8
 
 __global__ void __launch_bounds__(256, 2)
@@ -35,12 +35,15 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
                 const uint16_t *__restrict__ V, uint16_t *__restrict__ O, float *__restrict__ LSE,
                 const int32_t *__restrict__ seg_start, const int32_t *__restrict__ q_tile_order,
                 int N, int T, int tiles_per_row, int hq, int hkv, float scale_log2, float scale) {
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * (kLdsK + kLdsV)];
-  static_assert(2 * (kLdsK + kLdsV) * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit in the K/V buffers");
+  // stage 0 = {K, V} at lds[0 .. 2 kBlk), stage 1 = {K, V} at lds[2 kBlk .. 4 kBlk)
+  __shared__ __attribute__((aligned(16))) uint16_t lds[4 * kBlk];
+  static_assert(4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit in the K/V buffers");
 
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int l32 = lane & 31, half = lane >> 5;
-  const int tr_off = tr_lane_offset(lane, kVS);
+  const uint32_t row_lane = swz_row_lane_off(lane);
+  uint32_t tr_lane[2];
+  swz_tr_lane_off(lane, tr_lane);
 
   // heavy schedule tiles first; the workgroups of one schedule tile (sub-tiles x heads) are adjacent
   const int wg = xcd_group_remap(blockIdx.x, hq / hkv, gridDim.x);
@@ -88,103 +91,91 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   const size_t total = (size_t)N * row_bytes;
   const buffer_t kbuf = make_buffer((const char *)K + base_off, total - base_off);
   const buffer_t vbuf = make_buffer((const char *)V + base_off, total - base_off);
-  uint32_t ld_off[4];  // byte offset of this thread's 4 x 16 B inside a 64-row block
-  int st_k[4], st_v[4];
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int q = threadIdx.x + 256 * p;
-    ld_off[p] = (uint32_t)((q >> 4) * row_bytes + g * kD * 2 + (q & 15) * 16);
-    st_k[p] = (q >> 4) * kKS + (q & 15) * 8;
-    st_v[p] = (q >> 4) * kVS + (q & 15) * 8;
-  }
+  // HBM -> LDS copy of a 64-row block: 4 load instructions per wave and tensor, each writing 1 KB
+  // (4 rows) at wave-uniform LDS address (4 p + wave) KB; lane L lands at row 16 p + 4 wave + L / 16,
+  // chunk position L % 16, and therefore fetches global chunk (L % 16) ^ swz(row) of that row.
+  const int dma_row = wave * 4 + (lane >> 4);
+  const uint32_t dma_off = (uint32_t)(dma_row * row_bytes + g * kD * 2 + (((lane & 15) ^ swz(dma_row)) << 4));
   const uint32_t blk_bytes = (uint32_t)(kBN * row_bytes);
-
-  u32x4 rk[4], rv[4];
-#pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    rk[p] = buffer_load16(kbuf, ld_off[p]);
-    rv[p] = buffer_load16(vbuf, ld_off[p]);
-  }
-
-  for (int jb = jb_lo; jb <= jb_hi; ++jb) {  // bounds are workgroup-uniform: barriers stay aligned
-    uint16_t *Kb = lds + ((jb - jb_lo) & 1) * (kLdsK + kLdsV);
-    uint16_t *Vb = Kb + kLdsK;
-    // block jb: registers -> LDS buffer (its previous content, block jb-2, was consumed before the
-    // barrier of iteration jb-1); then start fetching block jb+1
+  const uint32_t p_bytes = (uint32_t)(16 * row_bytes);
+  typedef __attribute__((address_space(3))) void *lds_void;
+  auto copy_block = [&](uint16_t *Kd, uint16_t *Vd, int jb) {  // rows past the tensor arrive as zeros
+    const uint32_t off = dma_off + (uint32_t)(jb - jb_lo) * blk_bytes;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      *(u32x4 *)(Kb + st_k[p]) = rk[p];
-      *(u32x4 *)(Vb + st_v[p]) = rv[p];
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
     }
-    __syncthreads();
-    if (jb < jb_hi) {
-      const uint32_t off = (uint32_t)(jb + 1 - jb_lo) * blk_bytes;
-#pragma unroll
-      for (int p = 0; p < 4; ++p) {
-        rk[p] = buffer_load16(kbuf, ld_off[p] + off);
-        rv[p] = buffer_load16(vbuf, ld_off[p] + off);
-      }
-    }
-    const int j0 = jb * kBN;
-    if (!wave_ok || j0 > iw1 || j0 + kBN - 1 < ss_min) continue;  // wave-uniform
+  };
 
+  // One iteration: start the copy of block jb+1 into the other stage (last read before the previous
+  // barrier), consume block jb from (Kb, Vb); the barrier at the end publishes the copied block.
+  auto iteration = [&](int jb, const uint16_t *Kb, const uint16_t *Vb, uint16_t *Kn, uint16_t *Vn) {
+    if (jb < jb_hi) copy_block(Kn, Vn, jb + 1);  // workgroup-uniform
+    const int j0 = jb * kBN;
+    if (wave_ok && j0 <= iw1 && j0 + kBN - 1 >= ss_min) {  // wave-uniform
 #pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      const int jl = j0 + sb * 32;
-      if (jl > iw1 || jl + 31 < ss_min) continue;  // wave-uniform: sub-block outside this wave's keys
-      // ---- S^T = K Q^T ----
-      f32x16 s;
+      for (int sb = 0; sb < 2; ++sb) {
+        const int jl = j0 + sb * 32;
+        if (jl > iw1 || jl + 31 < ss_min) continue;  // wave-uniform: sub-block outside this wave's keys
+        // ---- S^T = K Q^T ----
+        f32x16 s;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) s[v] = 0.f;
+        for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 kf = as_bf16x8(*(const u32x4 *)(Kb + (sb * 32 + l32) * kKS + ks * 16 + half * 8));
-        s = mfma32(kf, qf[ks], s);
-      }
-      const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
-      if (!interior) {
+        for (int ks = 0; ks < 8; ++ks) s = mfma32(swz_read_row(Kb, row_lane, ks, sb * 32), qf[ks], s);
+        const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
+        if (!interior) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int j = jl + acc_row(v, half);
+            if (j < ss_i || j > i_abs) s[v] = -INFINITY;
+          }
+        }
+        // ---- online softmax with a lazily moved reference maximum ----
+        float mx = fmaxf(s[0], s[1]);
+#pragma unroll
+        for (int v = 2; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[v]), s[v + 1]);
+        mx = pair_max(mx);
+        if (__any((mx - m_ref) * scale_log2 > kLazyLog2)) {  // rare after the first block
+          const float m_new = fmaxf(m_ref, mx);
+          const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * scale_log2);
+          l_run *= alpha;
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o_acc[cb][v] *= alpha;
+          m_ref = m_new;
+        }
+        // rows with nothing unmasked so far have m_ref = -inf: use 0 so that exp2(-inf - 0) = 0
+        const float mneg = (m_ref == -INFINITY) ? 0.f : -m_ref * scale_log2;
+        float psum = 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int j = jl + acc_row(v, half);
-          if (j < ss_i || j > i_abs) s[v] = -INFINITY;
+          const float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, mneg));
+          s[v] = p;
+          psum += p;
         }
-      }
-      // ---- online softmax with a lazily moved reference maximum ----
-      float mx = fmaxf(s[0], s[1]);
+        l_run += psum;
+        // ---- O^T += V^T P^T ----
 #pragma unroll
-      for (int v = 2; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[v]), s[v + 1]);
-      mx = pair_max(mx);
-      if (__any((mx - m_ref) * scale_log2 > kLazyLog2)) {  // rare after the first block
-        const float m_new = fmaxf(m_ref, mx);
-        const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * scale_log2);
-        l_run *= alpha;
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 pf = pack_bf16x8(s, 8 * s2);
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) o_acc[cb][v] *= alpha;
-        m_ref = m_new;
-      }
-      // rows with nothing unmasked so far have m_ref = -inf: use 0 so that exp2(-inf - 0) = 0
-      const float mneg = (m_ref == -INFINITY) ? 0.f : -m_ref * scale_log2;
-      float psum = 0.f;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, mneg));
-        s[v] = p;
-        psum += p;
-      }
-      l_run += psum;
-      // ---- O^T += V^T P^T ----
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const bf16x8 pf = pack_bf16x8(s, 8 * s2);
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb) {
-          const bf16x8 vf = lds_read_tr8(Vb + tr_off + (sb * 32 + s2 * 16) * kVS + cb * 32, 8 * kVS);
-          o_acc[cb] = mfma32(vf, pf, o_acc[cb]);
+          for (int cb = 0; cb < 4; ++cb)
+            o_acc[cb] = mfma32(swz_read_tr(Vb, tr_lane, cb, sb * 32 + s2 * 16), pf, o_acc[cb]);
         }
       }
     }
+    __syncthreads();
+  };
+
+  uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
+  copy_block(K0, V0, jb_lo);
+  __syncthreads();
+  for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
+    iteration(jb, K0, V0, K1, V1);
+    if (jb + 1 <= jb_hi) iteration(jb + 1, K1, V1, K0, V0);
   }
 
   // ---- epilogue: normalise, stage O through LDS, coalesced stores ----
