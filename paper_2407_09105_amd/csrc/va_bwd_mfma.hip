@@ -93,70 +93,69 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   const size_t total = (size_t)N * row_bytes;
   const buffer_t kbuf = make_buffer((const char *)K + base_off, total - base_off);
   const buffer_t vbuf = make_buffer((const char *)V + base_off, total - base_off);
-  uint32_t ld_off[Copy::kPer], st_off[Copy::kPer];
-#pragma unroll
-  for (int p = 0; p < Copy::kPer; ++p) {
-    ld_off[p] = Copy::global_off(p, row_bytes, g);
-    st_off[p] = Copy::lds_off(p);
-  }
+  // HBM -> LDS copy of a 64-row block by the load unit (see the forward kernel): 4 loads per wave and
+  // tensor, each 1 KB = 4 rows at LDS address (4 p + wave) KB; lane L lands at row 16 p + 4 wave + L / 16,
+  // chunk position L % 16, and fetches global chunk (L % 16) ^ swz(row).
+  const int dma_row = wave * 4 + (lane >> 4);
+  const uint32_t dma_off = (uint32_t)(dma_row * row_bytes + g * kD * 2 + (((lane & 15) ^ swz(dma_row)) << 4));
   const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
-  u32x4 rk[Copy::kPer], rv[Copy::kPer];
+  const uint32_t p_bytes = (uint32_t)(16 * row_bytes);
+  typedef __attribute__((address_space(3))) void *lds_void;
+  auto copy_block = [&](uint16_t *Kd, uint16_t *Vd, int jb) {  // rows past the tensor arrive as zeros
+    const uint32_t off = dma_off + (uint32_t)(jb - jb_lo) * blk_bytes;
 #pragma unroll
-  for (int p = 0; p < Copy::kPer; ++p) {
-    rk[p] = buffer_load16(kbuf, ld_off[p]);
-    rv[p] = buffer_load16(vbuf, ld_off[p]);
-  }
+    for (int p = 0; p < 4; ++p) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
+    }
+  };
 
-  for (int jb = jb_lo; jb <= jb_hi; ++jb) {  // bounds are workgroup-uniform: barriers stay aligned
-    uint16_t *Kb = lds + ((jb - jb_lo) & 1) * 2 * kBlk;
-    uint16_t *Vb = Kb + kBlk;
+  // One iteration: start the copy of block jb+1 into the other stage (last read before the previous
+  // barrier), consume block jb from (Kb, Vb); the barrier at the end publishes the copied block.
+  auto iteration = [&](int jb, const uint16_t *Kb, const uint16_t *Vb, uint16_t *Kn, uint16_t *Vn) {
+    if (jb < jb_hi) copy_block(Kn, Vn, jb + 1);  // workgroup-uniform
+    const int j0 = jb * kBS;
+    if (wave_ok && j0 <= iw1 && j0 + kBS - 1 >= ss_min) {  // wave-uniform
 #pragma unroll
-    for (int p = 0; p < Copy::kPer; ++p) {
-      *(u32x4 *)((char *)Kb + st_off[p]) = rk[p];
-      *(u32x4 *)((char *)Vb + st_off[p]) = rv[p];
+      for (int sb = 0; sb < 2; ++sb) {
+        const int jl = j0 + sb * 32;
+        if (jl > iw1 || jl + 31 < ss_min) continue;  // wave-uniform
+        f32x16 s, dp;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) {
+          s = mfma32(swz_read_row(Kb, row_lane, ks, sb * 32), qf[ks], s);     // S^T  = K Q^T
+          dp = mfma32(swz_read_row(Vb, row_lane, ks, sb * 32), gf[ks], dp);   // dP^T = V dO^T
+        }
+        const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -lse2));
+          if (!interior) {
+            const int j = jl + acc_row(v, half);
+            if (j < ss_i || j > i_abs) p = 0.f;
+          }
+          s[v] = p * (dp[v] - dl);  // dS^T
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const bf16x8 df = pack_bf16x8(s, 8 * s2);
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb)  // dQ^T += K^T dS^T
+            acc[cb] = mfma32(swz_read_tr(Kb, tr_lane, cb, sb * 32 + s2 * 16), df, acc[cb]);
+        }
+      }
     }
     __syncthreads();
-    if (jb < jb_hi) {
-      const uint32_t off = (uint32_t)(jb + 1 - jb_lo) * blk_bytes;
-#pragma unroll
-      for (int p = 0; p < Copy::kPer; ++p) {
-        rk[p] = buffer_load16(kbuf, ld_off[p] + off);
-        rv[p] = buffer_load16(vbuf, ld_off[p] + off);
-      }
-    }
-    const int j0 = jb * kBS;
-    if (!wave_ok || j0 > iw1 || j0 + kBS - 1 < ss_min) continue;  // wave-uniform
+  };
 
-#pragma unroll
-    for (int sb = 0; sb < 2; ++sb) {
-      const int jl = j0 + sb * 32;
-      if (jl > iw1 || jl + 31 < ss_min) continue;  // wave-uniform
-      f32x16 s, dp;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
-#pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        s = mfma32(swz_read_row(Kb, row_lane, ks, sb * 32), qf[ks], s);     // S^T  = K Q^T
-        dp = mfma32(swz_read_row(Vb, row_lane, ks, sb * 32), gf[ks], dp);   // dP^T = V dO^T
-      }
-      const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -lse2));
-        if (!interior) {
-          const int j = jl + acc_row(v, half);
-          if (j < ss_i || j > i_abs) p = 0.f;
-        }
-        s[v] = p * (dp[v] - dl);  // dS^T
-      }
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2) {
-        const bf16x8 df = pack_bf16x8(s, 8 * s2);
-#pragma unroll
-        for (int cb = 0; cb < 4; ++cb)  // dQ^T += K^T dS^T
-          acc[cb] = mfma32(swz_read_tr(Kb, tr_lane, cb, sb * 32 + s2 * 16), df, acc[cb]);
-      }
-    }
+  uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
+  copy_block(K0, V0, jb_lo);
+  __syncthreads();
+  for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
+    iteration(jb, K0, V0, K1, V1);
+    if (jb + 1 <= jb_hi) iteration(jb + 1, K1, V1, K0, V0);
   }
 
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
