@@ -299,69 +299,64 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const size_t total = (size_t)N * row_bytes;
   const buffer_t qbuf = make_buffer((const char *)Q + base_off, total - base_off);
   const buffer_t gbuf = make_buffer((const char *)dO + base_off, total - base_off);
-  uint32_t ld_off[Copy::kPer], st_off[Copy::kPer];
-#pragma unroll
-  for (int p = 0; p < Copy::kPer; ++p) {
-    ld_off[p] = Copy::global_off(p, row_bytes, 0);
-    st_off[p] = Copy::lds_off(p);
-  }
+  // HBM -> LDS copy of a 64-row Q / dO block by the load unit (see the forward kernel)
+  const int dma_row = wave * 4 + (lane >> 4);
+  const uint32_t dma_off = (uint32_t)(dma_row * row_bytes + (((lane & 15) ^ swz(dma_row)) << 4));
   const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
-  // Two register sets: the block of iteration `it` travels HBM -> registers during iterations
-  // it-2 and it-1.  Every request is issued unconditionally (a block past the end is requested at
-  // an offset outside the buffer and returns zeros without touching memory) so that the number of
-  // outstanding requests is the same on every path and a wait can target the older set only.
-  struct Regs { u32x4 q[Copy::kPer], g[Copy::kPer]; float stat; };
+  const uint32_t p_bytes = (uint32_t)(16 * row_bytes);
+  typedef __attribute__((address_space(3))) void *lds_void;
   // iteration `it` streams query block ib_lo + it % nb of query head g * G + it / nb
   const int n_it = nb * G;
   const int stat_row = threadIdx.x & (kBS - 1);
   const bool stat_is_lse = (threadIdx.x & kBS) == 0;  // threads 0..63 (and 128..191): LSE; others: D
   const float *stat_src = stat_is_lse ? LSE : delta;
   const float stat_mul = stat_is_lse ? kLog2e : 1.f;
-  auto fetch = [&](Regs &rr, int it) {
-    const bool live = it < n_it;
-    const int hh = live ? it / nb : 0, ib = live ? ib_lo + it % nb : ib_lo;
-    const uint32_t off = (uint32_t)(ib - ib_lo) * blk_bytes + (uint32_t)((g * G + hh) * kD * 2);
-#pragma unroll
-    for (int p = 0; p < Copy::kPer; ++p) {
-      const uint32_t o = live ? ld_off[p] + off : kPastEnd;
-      rr.q[p] = buffer_load16(qbuf, o);
-      rr.g[p] = buffer_load16(gbuf, o);
-    }
+  float rstat;
+  auto copy_block = [&](uint16_t *dst, int it) {  // Q, dO blocks -> stage at dst; LSE / D value -> rstat
+    const int hh = it / nb, ib = ib_lo + it % nb;
     const int i = min(ib * kBS + stat_row, N - 1);
-    const size_t x = (size_t)(g * G + hh) * N + i;
-    rr.stat = stat_src[x];  // raw value; scaled when written to LDS (no use before the wait there)
-  };
-  auto iteration = [&](int it, Regs &rr) {  // rr holds the block of iteration `it`
-    uint16_t *Qs = lds + (it & 1) * kStage;
-    uint16_t *Gs = Qs + kBlk;
-    float *lse_s = (float *)(Gs + kBlk);  // [64] LSE * log2(e)
-    float *dl_s = lse_s + kBS;            // [64] D
-    // its LDS stage held the block of iteration it-2, consumed before the barrier of iteration it-1
+    rstat = stat_src[(size_t)(g * G + hh) * N + i];
+    const uint32_t off = dma_off + (uint32_t)(ib - ib_lo) * blk_bytes + (uint32_t)((g * G + hh) * kD * 2);
 #pragma unroll
-    for (int p = 0; p < Copy::kPer; ++p) {
-      *(u32x4 *)((char *)Qs + st_off[p]) = rr.q[p];
-      *(u32x4 *)((char *)Gs + st_off[p]) = rr.g[p];
-    }
-    if (threadIdx.x < 2 * kBS) lse_s[threadIdx.x] = rr.stat * stat_mul;
-    __syncthreads();
-    fetch(rr, it + 2);
-    const int i0 = (ib_lo + it % nb) * kBS;
-    if (!wave_ok || i0 + kBS - 1 < jw0 || i0 >= se_max) return;  // wave-uniform
-#pragma unroll 1  // one code instance: the accumulators keep their registers
-    for (int sb = 0; sb < 2; ++sb) {
-      const int il = i0 + sb * 32;
-      if (il + 31 < jw0 || il >= se_max) continue;  // wave-uniform
-      const bool interior = wave_full && il >= jw1 && il + 31 < se_min;
-      dkdv_subblock(!interior, dk_acc, dv_acc, kf, vf, Qs, Gs, lse_s, dl_s, sb * 32, row_lane, tr_lane, half, il,
-                    j_abs, se_j, scale_log2);
+    for (int p = 0; p < 4; ++p) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(qbuf, (lds_void)(dst + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(gbuf, (lds_void)(dst + kBlk + (4 * p + wave) * 512), 16,
+                                               off + p * p_bytes, 0, 0, 0);
     }
   };
-  Regs r0, r1;
-  fetch(r0, 0);
-  fetch(r1, 1);
+  auto put_stats = [&](uint16_t *dst) {  // [64] LSE * log2(e), [64] D behind the two blocks
+    if (threadIdx.x < 2 * kBS) ((float *)(dst + 2 * kBlk))[threadIdx.x] = rstat * stat_mul;
+  };
+
+  // One iteration: start the copy of the next block into the other stage (last read before the
+  // previous barrier), consume the current one, publish the next with the barrier at the end.
+  auto iteration = [&](int it, const uint16_t *cur, uint16_t *nxt) {
+    const bool more = it + 1 < n_it;  // workgroup-uniform
+    if (more) copy_block(nxt, it + 1);
+    const uint16_t *Qs = cur, *Gs = cur + kBlk;
+    const float *lse_s = (const float *)(cur + 2 * kBlk), *dl_s = lse_s + kBS;
+    const int i0 = (ib_lo + it % nb) * kBS;
+    if (wave_ok && i0 + kBS - 1 >= jw0 && i0 < se_max) {  // wave-uniform
+#pragma unroll 1  // one code instance per stage: the accumulators keep their registers
+      for (int sb = 0; sb < 2; ++sb) {
+        const int il = i0 + sb * 32;
+        if (il + 31 < jw0 || il >= se_max) continue;  // wave-uniform
+        const bool interior = wave_full && il >= jw1 && il + 31 < se_min;
+        dkdv_subblock(!interior, dk_acc, dv_acc, kf, vf, Qs, Gs, lse_s, dl_s, sb * 32, row_lane, tr_lane, half, il,
+                      j_abs, se_j, scale_log2);
+      }
+    }
+    if (more) put_stats(nxt);
+    __syncthreads();
+  };
+
+  uint16_t *S0 = lds, *S1 = lds + kStage;
+  copy_block(S0, 0);
+  put_stats(S0);
+  __syncthreads();
   for (int it = 0; it < n_it; it += 2) {  // bounds are workgroup-uniform: barriers stay aligned
-    iteration(it, r0);
-    if (it + 1 < n_it) iteration(it + 1, r1);
+    iteration(it, S0, S1);
+    if (it + 1 < n_it) iteration(it + 1, S1, S0);
   }
 
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
