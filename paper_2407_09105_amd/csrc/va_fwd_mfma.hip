@@ -70,12 +70,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   const int i_ld = min(i_abs, t_last);  // clamped: loads stay in bounds, results of dead rows are dropped
   const int ss_i = row_ok ? seg_start[i_ld] : 0x7fffffff;
 
-  bf16x8 qf[8];  // B operands of S^T = K Q^T; 8 k-steps of 16
-  {
-    const uint16_t *qp = Q + ((size_t)i_ld * hq + h) * kD + half * 8;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(*(const u32x4 *)(qp + ks * 16));
-  }
+  bf16x8 qf[8];  // B operands of S^T = K Q^T; 8 k-steps of 16 (loaded below, behind the first block copy)
 
   f32x16 o_acc[4];
 #pragma unroll
@@ -171,7 +166,12 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   };
 
   uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
-  copy_block(K0, V0, jb_lo);
+  copy_block(K0, V0, jb_lo);  // in flight while the Q fragments are fetched
+  {
+    const uint16_t *qp = Q + ((size_t)i_ld * hq + h) * kD + half * 8;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(*(const u32x4 *)(qp + ks * 16));
+  }
   __syncthreads();
   for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
     iteration(jb, K0, V0, K1, V1);

@@ -233,10 +233,17 @@ __device__ __forceinline__ void load_rows_to_lds_transposed(const uint16_t *__re
 //   acc[cb][v] = R[row = lane % 32][col = 32 cb + acc_row(v, half)],   32 rows x 128 cols,
 // multiplies row `lane % 32` by `mul`, and writes rows 0..nrows-1 to out[(row0 + row) * H + head]
 // (a [N, H, 128] tensor) with coalesced stores.  The tile is staged through LDS in two halves of
-// 64 columns; `stage` is this wave's [32][kStageStride] float buffer.  Every wave of the
-// workgroup must call this together (it contains workgroup barriers).
+// 64 columns; `stage` is this wave's private [32][kStageStride] float buffer, so only wave-level
+// ordering is needed here (LDS operations of one wave execute in order).  The caller must have
+// passed a workgroup barrier after the last use of the memory `stage` overlays.
 constexpr int kStageStride = 64 + 4;
 constexpr int kStageFloatsPerWave = 32 * kStageStride;
+
+__device__ __forceinline__ void wave_lds_fence() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 template <bool kF32Out>
 __device__ __forceinline__ void store_transposed_tile(const f32x16 (&acc)[4], float mul, float *stage,
@@ -245,7 +252,7 @@ __device__ __forceinline__ void store_transposed_tile(const f32x16 (&acc)[4], fl
   const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
 #pragma unroll
   for (int p = 0; p < 2; ++p) {
-    __syncthreads();
+    wave_lds_fence();  // the reads of the previous half (or tile) are done before it is overwritten
 #pragma unroll
     for (int cc = 0; cc < 2; ++cc)
 #pragma unroll
@@ -255,7 +262,7 @@ __device__ __forceinline__ void store_transposed_tile(const f32x16 (&acc)[4], fl
         for (int b = 0; b < 4; ++b) w[b] = acc[2 * p + cc][4 * q4 + b] * mul;
         *(f32x4 *)(stage + l32 * kStageStride + cc * 32 + q4 * 8 + half * 4) = w;
       }
-    __syncthreads();
+    wave_lds_fence();
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
       const int rr = it * 4 + (lane >> 4), c4 = lane & 15;
