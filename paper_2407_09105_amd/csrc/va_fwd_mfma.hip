@@ -5,10 +5,12 @@
 // the position-id scan (paper, Section 3); keys of other examples are never attended (Table 1)
 // and key blocks that lie wholly outside [seg_start[first row], last row] are never loaded.
 //
-// Shape of the computation: one workgroup (4 waves) per (128-token query tile, query head), two
+// Shape of the computation: one workgroup (4 waves) per (128-token query tile, query head), three
 // workgroups resident per CU so that one wave's softmax (vector ALU) overlaps another wave's
 // MFMAs on the same SIMD.  Wave w owns query rows 32w..32w+31.  Key/value rows stream through
-// LDS in blocks of 64, double-buffered; the next block is copied HBM -> LDS by the load unit itself
+// LDS in blocks of 32, double-buffered (small stages and <= 168 registers keep three workgroups
+// resident per CU: short tiles are chains of dependent memory latencies that only other
+// workgroups can hide); the next block is copied HBM -> LDS by the load unit itself
 // (buffer loads with an LDS destination: no registers, no LDS store instructions) while the
 // current one is consumed.  Blocks are stored unpadded in the XOR-swizzled layout of
 // va_mfma_common.h; since such a load writes 64 consecutive 16-byte chunks, the swizzle is applied
@@ -26,18 +28,18 @@ namespace {
 
 constexpr int kBM = 128;          // query rows per workgroup
 constexpr int kSub = VA_TILE / kBM;
-constexpr int kBN = 64;           // key rows per LDS block
-constexpr int kBlk = kBN * kD;    // elements of one swizzled [64][128] LDS block (16 KB)
+constexpr int kBN = 32;           // key rows per LDS block
+constexpr int kBlk = kBN * kD;    // elements of one swizzled [32][128] LDS block (8 KB)
+constexpr int kLdsElems = (4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4) ? 4 * kBlk : 4 * kStageFloatsPerWave * 2;
 constexpr float kLazyLog2 = 8.f;  // keep a stale row maximum while probabilities stay <= 2^8
 
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256, 3)
 fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
                 const uint16_t *__restrict__ V, uint16_t *__restrict__ O, float *__restrict__ LSE,
                 const int32_t *__restrict__ seg_start, const int32_t *__restrict__ q_tile_order,
                 int N, int T, int tiles_per_row, int hq, int hkv, float scale_log2, float scale) {
   // stage 0 = {K, V} at lds[0 .. 2 kBlk), stage 1 = {K, V} at lds[2 kBlk .. 4 kBlk)
-  __shared__ __attribute__((aligned(16))) uint16_t lds[4 * kBlk];
-  static_assert(4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit in the K/V buffers");
+  __shared__ __attribute__((aligned(16))) uint16_t lds[kLdsElems];
 
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int l32 = lane & 31, half = lane >> 5;
@@ -86,8 +88,8 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   const size_t total = (size_t)N * row_bytes;
   const buffer_t kbuf = make_buffer((const char *)K + base_off, total - base_off);
   const buffer_t vbuf = make_buffer((const char *)V + base_off, total - base_off);
-  // HBM -> LDS copy of a 64-row block: 4 load instructions per wave and tensor, each writing 1 KB
-  // (4 rows) at wave-uniform LDS address (4 p + wave) KB; lane L lands at row 16 p + 4 wave + L / 16,
+  // HBM -> LDS copy of a kBN-row block: kBN / 16 load instructions per wave and tensor, each writing
+  // 1 KB (4 rows) at wave-uniform LDS address (4 p + wave) KB; lane L lands at row 16 p + 4 wave + L / 16,
   // chunk position L % 16, and therefore fetches global chunk (L % 16) ^ swz(row) of that row.
   const int dma_row = wave * 4 + (lane >> 4);
   const uint32_t dma_off = (uint32_t)(dma_row * row_bytes + g * kD * 2 + (((lane & 15) ^ swz(dma_row)) << 4));
@@ -97,7 +99,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   auto copy_block = [&](uint16_t *Kd, uint16_t *Vd, int jb) {  // rows past the tensor arrive as zeros
     const uint32_t off = dma_off + (uint32_t)(jb - jb_lo) * blk_bytes;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < kBN / 16; ++p) {
       __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
       __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
     }
@@ -110,7 +112,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const int j0 = jb * kBN;
     if (wave_ok && j0 <= iw1 && j0 + kBN - 1 >= ss_min) {  // wave-uniform
 #pragma unroll
-      for (int sb = 0; sb < 2; ++sb) {
+      for (int sb = 0; sb < kBN / 32; ++sb) {
         const int jl = j0 + sb * 32;
         if (jl > iw1 || jl + 31 < ss_min) continue;  // wave-uniform: sub-block outside this wave's keys
         // ---- S^T = K Q^T ----
