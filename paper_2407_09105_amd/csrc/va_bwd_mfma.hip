@@ -258,9 +258,42 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const int t0 = r * T + m * VA_TILE + sub * kBT;
   if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
   const int t_last = min(t0 + kBT, row_end) - 1;
-  // query blocks that can see a key of this tile: from the tile's first key to the end of the
-  // example holding its last key
-  const int ib_lo = t0 / kBS, ib_hi = (uniform(seg_end[t_last]) - 1) / kBS;
+  const int ib_lo = t0 / kBS;  // first query block that can see a key of this tile
+
+  const size_t row_bytes = (size_t)hq * kD * 2;
+  const size_t base_off = (size_t)ib_lo * kBS * row_bytes;
+  const size_t total = (size_t)N * row_bytes;
+  const buffer_t qbuf = make_buffer((const char *)Q + base_off, total - base_off);
+  const buffer_t gbuf = make_buffer((const char *)dO + base_off, total - base_off);
+  // HBM -> LDS copy of a 64-row Q / dO block by the load unit (see the forward kernel)
+  const int dma_row = wave * 4 + (lane >> 4);
+  const uint32_t dma_off = (uint32_t)(dma_row * row_bytes + (((lane & 15) ^ swz(dma_row)) << 4));
+  const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
+  const uint32_t p_bytes = (uint32_t)(16 * row_bytes);
+  typedef __attribute__((address_space(3))) void *lds_void;
+  const int stat_row = threadIdx.x & (kBS - 1);
+  const bool stat_is_lse = (threadIdx.x & kBS) == 0;  // threads 0..63 (and 128..191): LSE; others: D
+  const float *stat_src = stat_is_lse ? LSE : delta;
+  const float stat_mul = stat_is_lse ? kLog2e : 1.f;
+  float rstat;
+  // Q, dO blocks (query head g * G + hh, block ib) -> stage at dst; LSE / D value -> rstat
+  auto copy_block = [&](uint16_t *dst, int hh, int ib) {
+    const int i = min(ib * kBS + stat_row, N - 1);
+    rstat = stat_src[(size_t)(g * G + hh) * N + i];
+    const uint32_t off = dma_off + (uint32_t)(ib - ib_lo) * blk_bytes + (uint32_t)((g * G + hh) * kD * 2);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(qbuf, (lds_void)(dst + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(gbuf, (lds_void)(dst + kBlk + (4 * p + wave) * 512), 16,
+                                               off + p * p_bytes, 0, 0, 0);
+    }
+  };
+  // the first block needs nothing but the tile: its copy starts before the example bounds arrive
+  uint16_t *S0 = lds, *S1 = lds + kStage;
+  copy_block(S0, 0, ib_lo);
+
+  // query blocks end with the example holding the tile's last key
+  const int ib_hi = (uniform(seg_end[t_last]) - 1) / kBS;
   const int nb = ib_hi - ib_lo + 1;
 
   const int jw0 = t0 + wave * 32;
@@ -294,36 +327,8 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   uint32_t tr_lane[2];
   swz_tr_lane_off(lane, tr_lane);
 
-  const size_t row_bytes = (size_t)hq * kD * 2;
-  const size_t base_off = (size_t)ib_lo * kBS * row_bytes;
-  const size_t total = (size_t)N * row_bytes;
-  const buffer_t qbuf = make_buffer((const char *)Q + base_off, total - base_off);
-  const buffer_t gbuf = make_buffer((const char *)dO + base_off, total - base_off);
-  // HBM -> LDS copy of a 64-row Q / dO block by the load unit (see the forward kernel)
-  const int dma_row = wave * 4 + (lane >> 4);
-  const uint32_t dma_off = (uint32_t)(dma_row * row_bytes + (((lane & 15) ^ swz(dma_row)) << 4));
-  const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
-  const uint32_t p_bytes = (uint32_t)(16 * row_bytes);
-  typedef __attribute__((address_space(3))) void *lds_void;
   // iteration `it` streams query block ib_lo + it % nb of query head g * G + it / nb
   const int n_it = nb * G;
-  const int stat_row = threadIdx.x & (kBS - 1);
-  const bool stat_is_lse = (threadIdx.x & kBS) == 0;  // threads 0..63 (and 128..191): LSE; others: D
-  const float *stat_src = stat_is_lse ? LSE : delta;
-  const float stat_mul = stat_is_lse ? kLog2e : 1.f;
-  float rstat;
-  auto copy_block = [&](uint16_t *dst, int it) {  // Q, dO blocks -> stage at dst; LSE / D value -> rstat
-    const int hh = it / nb, ib = ib_lo + it % nb;
-    const int i = min(ib * kBS + stat_row, N - 1);
-    rstat = stat_src[(size_t)(g * G + hh) * N + i];
-    const uint32_t off = dma_off + (uint32_t)(ib - ib_lo) * blk_bytes + (uint32_t)((g * G + hh) * kD * 2);
-#pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(qbuf, (lds_void)(dst + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(gbuf, (lds_void)(dst + kBlk + (4 * p + wave) * 512), 16,
-                                               off + p * p_bytes, 0, 0, 0);
-    }
-  };
   auto put_stats = [&](uint16_t *dst) {  // [64] LSE * log2(e), [64] D behind the two blocks
     if (threadIdx.x < 2 * kBS) ((float *)(dst + 2 * kBlk))[threadIdx.x] = rstat * stat_mul;
   };
@@ -332,7 +337,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   // previous barrier), consume the current one, publish the next with the barrier at the end.
   auto iteration = [&](int it, const uint16_t *cur, uint16_t *nxt) {
     const bool more = it + 1 < n_it;  // workgroup-uniform
-    if (more) copy_block(nxt, it + 1);
+    if (more) copy_block(nxt, (it + 1) / nb, ib_lo + (it + 1) % nb);
     const uint16_t *Qs = cur, *Gs = cur + kBlk;
     const float *lse_s = (const float *)(cur + 2 * kBlk), *dl_s = lse_s + kBS;
     const int i0 = (ib_lo + it % nb) * kBS;
@@ -350,8 +355,6 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
     __syncthreads();
   };
 
-  uint16_t *S0 = lds, *S1 = lds + kStage;
-  copy_block(S0, 0);
   put_stats(S0);
   __syncthreads();
   for (int it = 0; it < n_it; it += 2) {  // bounds are workgroup-uniform: barriers stay aligned
