@@ -112,7 +112,8 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 
   // One iteration: start the copy of block jb+1 into the other stage (last read before the previous
   // barrier), consume block jb from (Kb, Vb); the barrier at the end publishes the copied block.
-  auto iteration = [&](int jb, const uint16_t *Kb, const uint16_t *Vb, uint16_t *Kn, uint16_t *Vn) {
+  auto iteration = [&](int jb, const uint16_t *__restrict__ Kb, const uint16_t *__restrict__ Vb,
+                       uint16_t *__restrict__ Kn, uint16_t *__restrict__ Vn) {
     if (jb < jb_hi) copy_block(Kn, Vn, jb + 1);  // workgroup-uniform
     const int j0 = jb * kBS;
     if (wave_ok && j0 <= iw1 && j0 + kBS - 1 >= ss_min) {  // wave-uniform
@@ -152,6 +153,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 
   uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
   copy_block(K0, V0, jb_lo);
+  wait_all_loads();  // Q / dO fragments too: inside the loop only block copies are in flight
   __syncthreads();
   for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
     iteration(jb, K0, V0, K1, V1);
@@ -335,7 +337,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 
   // One iteration: start the copy of the next block into the other stage (last read before the
   // previous barrier), consume the current one, publish the next with the barrier at the end.
-  auto iteration = [&](int it, const uint16_t *cur, uint16_t *nxt) {
+  auto iteration = [&](int it, const uint16_t *__restrict__ cur, uint16_t *__restrict__ nxt) {
     const bool more = it + 1 < n_it;  // workgroup-uniform
     if (more) copy_block(nxt, (it + 1) / nb, ib_lo + (it + 1) % nb);
     const uint16_t *Qs = cur, *Gs = cur + kBlk;
@@ -356,6 +358,9 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   };
 
   put_stats(S0);
+  // every load issued so far (K/V fragments included) lands here: inside the loop only the block
+  // copies are in flight, and nothing but the barrier waits for them
+  wait_all_loads();
   __syncthreads();
   for (int it = 0; it < n_it; it += 2) {  // bounds are workgroup-uniform: barriers stay aligned
     iteration(it, S0, S1);

@@ -107,7 +107,8 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
 
   // One iteration: start the copy of block jb+1 into the other stage (last read before the previous
   // barrier), consume block jb from (Kb, Vb); the barrier at the end publishes the copied block.
-  auto iteration = [&](int jb, const uint16_t *Kb, const uint16_t *Vb, uint16_t *Kn, uint16_t *Vn) {
+  auto iteration = [&](int jb, const uint16_t *__restrict__ Kb, const uint16_t *__restrict__ Vb,
+                       uint16_t *__restrict__ Kn, uint16_t *__restrict__ Vn) {
     if (jb < jb_hi) copy_block(Kn, Vn, jb + 1);  // workgroup-uniform
     const int j0 = jb * kBN;
     if (wave_ok && j0 <= iw1 && j0 + kBN - 1 >= ss_min) {  // wave-uniform
@@ -174,6 +175,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(*(const u32x4 *)(qp + ks * 16));
   }
+  wait_all_loads();  // Q fragments too: inside the loop only block copies are in flight
   __syncthreads();
   for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
     iteration(jb, K0, V0, K1, V1);

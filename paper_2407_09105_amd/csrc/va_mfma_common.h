@@ -81,6 +81,10 @@ __device__ __forceinline__ bf16x8 lds_read_tr8(const uint16_t *p, int second) {
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// s_waitcnt vmcnt(0), visible to the compiler's wait-count bookkeeping (expcnt and lgkmcnt fields
+// left at their maxima: 7 << 4, 15 << 8).
+__device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 // Workgroups are handed to the 8 XCDs (each with its own L2) round-robin by workgroup id.  With
 // grouped-query attention the G query heads of one KV head stream the same K/V blocks; this maps
 // workgroup id -> logical index so that G consecutive logical indices (the heads of one group, which
