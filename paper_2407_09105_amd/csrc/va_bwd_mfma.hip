@@ -172,26 +172,26 @@ __device__ __forceinline__ void dkdv_subblock(bool need_mask, f32x16 (&dk_acc)[4
                                               const float *lse_s, const float *dl_s, int row0, uint32_t row_lane,
                                               const uint32_t (&tr_lane)[2], int half, int il, int j_abs, int se_j,
                                               float scale_log2) {
+  // the accumulators start from the per-query constants: S from -LSE / scale, dP from -D
+  f32x16 s, dp;
+#pragma unroll
+  for (int q4 = 0; q4 < 4; ++q4) {
+    const f32x4 l = *(const f32x4 *)(lse_s + row0 + q4 * 8 + half * 4);
+    const f32x4 d = *(const f32x4 *)(dl_s + row0 + q4 * 8 + half * 4);
+#pragma unroll
+    for (int b = 0; b < 4; ++b) { s[q4 * 4 + b] = l[b]; dp[q4 * 4 + b] = d[b]; }
+  }
   bf16x8 aq[8], ag[8];
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
     aq[ks] = swz_read_row(Qs, row_lane, ks, row0);
     ag[ks] = swz_read_row(Gs, row_lane, ks, row0);
   }
-  f32x4 l4[4], d4[4];
-#pragma unroll
-  for (int q4 = 0; q4 < 4; ++q4) {
-    l4[q4] = *(const f32x4 *)(lse_s + row0 + q4 * 8 + half * 4);
-    d4[q4] = *(const f32x4 *)(dl_s + row0 + q4 * 8 + half * 4);
-  }
   __builtin_amdgcn_sched_barrier(0);  // keep every read above in flight before the first MFMA
-  f32x16 s, dp;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
   for (int ks = 0; ks < 8; ++ks) {
-    s = mfma32(aq[ks], kf[ks], s);     // S  = Q K^T
-    dp = mfma32(ag[ks], vf[ks], dp);   // dP = dO V^T
+    s = mfma32(aq[ks], kf[ks], s);     // S - LSE / scale  = Q K^T - LSE / scale
+    dp = mfma32(ag[ks], vf[ks], dp);   // dP - D           = dO V^T - D
   }
   bf16x8 tq[2][4], tg[2][4];
 #pragma unroll
@@ -203,12 +203,7 @@ __device__ __forceinline__ void dkdv_subblock(bool need_mask, f32x16 (&dk_acc)[4
     }
   __builtin_amdgcn_sched_barrier(0);  // transposed fragments land while the arithmetic below runs
 #pragma unroll
-  for (int q4 = 0; q4 < 4; ++q4)
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int v = q4 * 4 + b;
-      s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -l4[q4][b]));  // P
-    }
+  for (int v = 0; v < 16; ++v) s[v] = __builtin_amdgcn_exp2f(s[v] * scale_log2);  // P
   if (need_mask) {  // wave-uniform; touches only the probabilities
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
@@ -217,12 +212,7 @@ __device__ __forceinline__ void dkdv_subblock(bool need_mask, f32x16 (&dk_acc)[4
     }
   }
 #pragma unroll
-  for (int q4 = 0; q4 < 4; ++q4)
-#pragma unroll
-    for (int b = 0; b < 4; ++b) {
-      const int v = q4 * 4 + b;
-      dp[v] = s[v] * (dp[v] - d4[q4][b]);  // dS
-    }
+  for (int v = 0; v < 16; ++v) dp[v] *= s[v];  // dS
 #pragma unroll
   for (int s2 = 0; s2 < 2; ++s2) {
     const bf16x8 pf = pack_bf16x8(s, 8 * s2);
@@ -244,7 +234,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
                  void *__restrict__ dV, const int32_t *__restrict__ seg_end,
                  const int32_t *__restrict__ kv_tile_order, int N, int T, int tiles_per_row, int hq,
                  int hkv, float scale_log2, float scale) {
-  // two stages of {Q block, dO block (swizzled), LSE * log2(e) [64], D [64]}
+  // two stages of {Q block, dO block (swizzled), -LSE / scale [64], -D [64]}
   constexpr int kStage = 2 * kBlk + 4 * kBS;  // elements (floats take two)
   __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kStage];
   static_assert(2 * kStage * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit");
@@ -276,7 +266,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const int stat_row = threadIdx.x & (kBS - 1);
   const bool stat_is_lse = (threadIdx.x & kBS) == 0;  // threads 0..63 (and 128..191): LSE; others: D
   const float *stat_src = stat_is_lse ? LSE : delta;
-  const float stat_mul = stat_is_lse ? kLog2e : 1.f;
+  const float stat_mul = stat_is_lse ? -1.f / scale : -1.f;
   float rstat;
   // Q, dO blocks (query head g * G + hh, block ib) -> stage at dst; LSE / D value -> rstat
   auto copy_block = [&](uint16_t *dst, int hh, int ib) {
@@ -331,18 +321,21 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 
   // iteration `it` streams query block ib_lo + it % nb of query head g * G + it / nb
   const int n_it = nb * G;
-  auto put_stats = [&](uint16_t *dst) {  // [64] LSE * log2(e), [64] D behind the two blocks
+  auto put_stats = [&](uint16_t *dst) {  // [64] -LSE / scale, [64] -D behind the two blocks
     if (threadIdx.x < 2 * kBS) ((float *)(dst + 2 * kBlk))[threadIdx.x] = rstat * stat_mul;
   };
 
   // One iteration: start the copy of the next block into the other stage (last read before the
   // previous barrier), consume the current one, publish the next with the barrier at the end.
+  int ib_cur = ib_lo, ib_nxt = ib_lo, hh_nxt = 0;  // block being consumed; block / head being copied
   auto iteration = [&](int it, const uint16_t *__restrict__ cur, uint16_t *__restrict__ nxt) {
     const bool more = it + 1 < n_it;  // workgroup-uniform
-    if (more) copy_block(nxt, (it + 1) / nb, ib_lo + (it + 1) % nb);
+    if (++ib_nxt > ib_hi) { ib_nxt = ib_lo; ++hh_nxt; }
+    if (more) copy_block(nxt, hh_nxt, ib_nxt);
     const uint16_t *Qs = cur, *Gs = cur + kBlk;
     const float *lse_s = (const float *)(cur + 2 * kBlk), *dl_s = lse_s + kBS;
-    const int i0 = (ib_lo + it % nb) * kBS;
+    const int i0 = ib_cur * kBS;
+    ib_cur = ib_nxt;
     if (wave_ok && i0 + kBS - 1 >= jw0 && i0 < se_max) {  // wave-uniform
 #pragma unroll 1  // one code instance per stage: the accumulators keep their registers
       for (int sb = 0; sb < 2; ++sb) {
