@@ -60,6 +60,27 @@ def pack(position_ids: np.ndarray):
     }
 
 
+def collate(ids_padded, lengths, n_out, labels_padded=None, pad_id=0):
+    """Padding-free collator (Section 3.4) on a padded [n, Lp] batch -> dict(input_ids, labels,
+    position_ids: int64 [n_out]; offsets int32 [n+1])."""
+    ids = np.ascontiguousarray(ids_padded, dtype=np.int64)
+    assert ids.ndim == 2
+    n, Lp = ids.shape
+    lab = None if labels_padded is None else np.ascontiguousarray(labels_padded, dtype=np.int64)
+    lengths = np.ascontiguousarray(lengths, dtype=np.int32)
+    assert lengths.shape == (n,)
+    out = {k: np.full(n_out, -7, dtype=np.int64) for k in ("input_ids", "labels", "position_ids")}
+    offsets = np.zeros(n + 1, dtype=np.int32)
+    rc = lib().oracle_collate(_p(ids, C.c_int64), None if lab is None else _p(lab, C.c_int64),
+                              _p(lengths, C.c_int32), C.c_int(n), C.c_int(Lp), C.c_int64(n_out),
+                              C.c_int64(pad_id), _p(out["input_ids"], C.c_int64), _p(out["labels"], C.c_int64),
+                              _p(out["position_ids"], C.c_int64), _p(offsets, C.c_int32))
+    if rc != 0:
+        raise RuntimeError(f"oracle_collate failed: {rc}")
+    out["offsets"] = offsets
+    return out
+
+
 def _dims(q, k):
     N, Hq, d = q.shape
     Nk, Hkv, dk = k.shape

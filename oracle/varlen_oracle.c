@@ -27,7 +27,12 @@
  * Layouts: Q, O, dO, dQ  [N, Hq, d];  K, V, dK, dV  [N, Hkv, d];  LSE [Hq, N]; all
  * row-major doubles.  No blocking, fusion or reordering beyond the above.
  *
- * Pins (tests/test_oracle_*.py): the paper's worked example (Section 3.5),
+ * The padding-free collator (Section 3.4) that produces the ids is written out
+ * as its three rules (concatenate; first label of an example -> -100; ids
+ * restart at 0) -- see oracle_collate.
+ *
+ * Pins (tests/test_oracle_*.py): the paper's worked example (Section 3.5: printed
+ * input_ids, labels, position_ids pin the collator and the boundaries),
  * brute-force dense masked attention, per-example unpacking, perturbation of
  * other examples, closed forms (length-1 example, Q = 0 running mean), central
  * finite differences, and a library attention routine on one example.
@@ -58,6 +63,49 @@ int oracle_pack(const int64_t *pos, int R, int T, int32_t *cu, int32_t *seg_id,
         if (cu[s + 1] - cu[s] > mx) mx = cu[s + 1] - cu[s];
     *n_out = n;
     *max_seqlen_out = mx;
+    return 0;
+}
+
+/* ---- padding-free collator -------------------------------------------- */
+
+/* The collator of Section 3.4 on a minibatch given as a padded [n, Lp] batch
+ * with per-example lengths: concatenate the examples into one row of n_out
+ * tokens.  input_ids: the tokens in order.  labels: the labels (labels_in, or
+ * the ids when labels_in is NULL) with the first label of every example set to
+ * -100.  position_ids: 0..L-1 inside every example.  (Section 3.5 prints all
+ * three for lengths 4, 8, 5, 11.)  offsets[n+1]: running sum of the lengths.
+ * Readings where the paper is silent: a length outside [0, Lp] is clamped; if
+ * the lengths sum to less than n_out the tail is one pad pseudo-example
+ * (pad_id, label -100, ids 0, 1, 2, ...); if to more, the stream is cut at
+ * n_out (the last example is broken, as fixed-length packing does, Table 1). */
+int oracle_collate(const int64_t *ids, const int64_t *labels_in, const int32_t *lengths,
+                   int n, int Lp, int64_t n_out, int64_t pad_id, int64_t *input_ids,
+                   int64_t *labels, int64_t *position_ids, int32_t *offsets)
+{
+    if (!ids || !lengths || !input_ids || !labels || !position_ids || !offsets || n < 0 || Lp <= 0 ||
+        n_out < 0)
+        return 1;
+    int64_t t = 0, total = 0;
+    offsets[0] = 0;
+    for (int e = 0; e < n; ++e) {
+        int32_t L = lengths[e];
+        if (L < 0) L = 0;
+        if (L > Lp) L = Lp;
+        for (int32_t p = 0; p < L; ++p, ++t) {
+            if (t >= n_out) continue;
+            const int64_t src = (int64_t)e * Lp + p;
+            input_ids[t] = ids[src];
+            labels[t] = p == 0 ? -100 : (labels_in ? labels_in[src] : ids[src]);
+            position_ids[t] = p;
+        }
+        total += L;
+        offsets[e + 1] = (int32_t)total;
+    }
+    for (int64_t p = 0; t < n_out; ++t, ++p) {
+        input_ids[t] = pad_id;
+        labels[t] = -100;
+        position_ids[t] = p;
+    }
     return 0;
 }
 
