@@ -36,6 +36,7 @@ def parse_args():
     ap.add_argument("--config", type=int, default=2, help="workload (index into the config table, 2..5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the no-position-id and collator timings")
     ap.add_argument("--cpu-heads", type=int, default=0, help="query heads in the CPU-oracle sample (0 = auto)")
     return ap.parse_args()
 
@@ -121,6 +122,40 @@ def padded_run(torch, binding, wl, w, q, k, v, do):
 
     run = GpuRun(torch, binding, pos, pad(q), pad(k), pad(v), pad(do))
     return run, n_pad, ir, ip
+
+
+def no_posid_run(torch, binding, w, q, k, v, do):
+    """The same packed rows with position ids that never restart (0..T-1 per row): what fixed-length
+    packing without position ids computes (Table 1: cross-contaminated attention).  One example per
+    row, so no key tile is skipped; useful FLOPs counted are still those of the real examples."""
+    cfg = w.cfg
+    pos = np.tile(np.arange(cfg.tokens_per_row, dtype=np.int64), (cfg.rows, 1))
+    return GpuRun(torch, binding, pos, q, k, v, do)
+
+
+def collate_timing(torch, binding, w, steps):
+    """Device collator (padded batch -> input_ids, labels, position_ids) on the workload's first row."""
+    lengths = np.array(w.lengths[0], dtype=np.int32)
+    n, Lp, T = len(lengths), int(lengths.max()), w.cfg.tokens_per_row
+    g = torch.Generator(device="cuda"); g.manual_seed(7)
+    ids = torch.randint(0, 32000, (n, Lp), device="cuda", generator=g, dtype=torch.int64)
+    ln = torch.from_numpy(lengths).cuda()
+    out = binding.collate_padding_free(ids, ln, T)
+    for _ in range(3):
+        binding.collate_padding_free(ids, ln, T, out=out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        binding.collate_padding_free(ids, ln, T, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    algo_bytes = T * 8 + n * 4 + 3 * T * 8 + (n + 1) * 4   # ids read once, lengths, three outputs, offsets
+    ok = bool((out["position_ids"].cpu().numpy() == w.position_ids[:1]).all())
+    return {"ms": ms, "examples": n, "padded_len": Lp, "tokens": T, "algorithmic_bytes": algo_bytes,
+            "achieved_GBs": algo_bytes / (ms * 1e-3) / 1e9, "frac_hbm_peak": algo_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            "bound": "launch latency (two tiny kernels)", "position_ids_match_workload": ok}
 
 
 def cpu_baseline(wl, cfg_id, heads):
@@ -245,6 +280,17 @@ def main():
             "tokens_per_s": cfg.n_tokens / (pms * 1e-3), "packing_gain": pms / ms_plain,
         }
         del prun
+    if not args.no_extras:
+        nrun = no_posid_run(torch, binding, w, q, k, v, do)
+        nms, _ = timed(torch, nrun, max(5, args.steps // 2), 3, with_events=False)
+        del nrun
+        T = cfg.tokens_per_row
+        out["no_position_ids"] = {
+            "layout": "same rows, ids 0..T-1 (one example per row: attention crosses example boundaries)",
+            "ms_per_step": nms, "value": useful / (nms * 1e-3) / 1e12, "unit": "TFLOP/s (useful)",
+            "executed_pairs_per_head": cfg.rows * T * (T + 1) // 2, "position_id_gain": nms / ms_plain,
+        }
+        out["collate"] = collate_timing(torch, binding, w, args.steps)
     if not args.no_cpu_baseline:
         heads = args.cpu_heads or {2: 32, 3: 16, 4: 32, 5: 0}.get(cfg_id, 8)
         if heads:

@@ -88,6 +88,32 @@ va_status va_segments_bind(void *plan, size_t plan_bytes, int32_t rows, int32_t 
 va_status va_pack_to_cu_seqlens(const void *position_ids, va_itype it, int32_t rows,
                                 int32_t tokens_per_row, const va_segments *seg, void *stream);
 
+/*
+ * Padding-free collator on the device (paper, Section 3.4; worked example in Section 3.5): the
+ * step that produces the position ids the call above consumes.  A minibatch of n_examples
+ * examples, held as a padded batch with per-example lengths, is concatenated into ONE packed row
+ * of n_out tokens:
+ *     input_ids     the tokens of the examples in order
+ *     labels        their labels (labels_padded, or the ids when that is NULL) with the first
+ *                   label of every example replaced by -100
+ *     position_ids  0 .. L-1 inside every example
+ *   ids_padded, labels_padded : device, [n_examples, padded_len] of `it`; entries past an example's
+ *                   length are never read.  labels_padded may be NULL.
+ *   lengths       : device, [n_examples] int32; values outside [0, padded_len] are clamped.
+ *   n_out         : tokens in the packed row; normally the sum of the lengths.  If the lengths
+ *                   sum to less, the tail is one pad pseudo-example (pad_id, label -100, ids
+ *                   0, 1, 2, ...); if to more, the row is cut at n_out (the last example is
+ *                   broken, as fixed-length packing does: Table 1).
+ *   input_ids, labels, position_ids : device, [n_out] of `it`, fully overwritten.
+ *   example_offsets : device, [n_examples + 1] int32: running sum of the clamped lengths
+ *                   (example_offsets[n_examples] = their total, not clipped to n_out).
+ * n_examples * padded_len must stay below 2^31 - 1 (VA_ERR_SHAPE).  Integer work only; exact.
+ */
+va_status va_collate_padding_free(const void *ids_padded, const void *labels_padded, va_itype it,
+                                  const int32_t *lengths, int32_t n_examples, int32_t padded_len,
+                                  int32_t n_out, int64_t pad_id, void *input_ids, void *labels,
+                                  void *position_ids, int32_t *example_offsets, void *stream);
+
 /* Workspace bytes for one forward (is_bwd = 0) or backward (is_bwd = 1) call (0 on bad shape). */
 size_t va_attn_workspace_bytes(int32_t n_tokens, int32_t hq, int32_t hkv, int32_t d, int is_bwd);
 

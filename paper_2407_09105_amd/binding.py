@@ -24,7 +24,8 @@ STAGE_D, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 
 EXPORTS = (
     "va_plan_bytes", "va_segments_bind", "va_pack_to_cu_seqlens", "va_attn_workspace_bytes",
-    "va_varlen_attn_fwd", "va_varlen_attn_bwd", "va_varlen_attn_bwd_stages", "va_status_string", "va_version",
+    "va_varlen_attn_fwd", "va_varlen_attn_bwd", "va_varlen_attn_bwd_stages", "va_collate_padding_free",
+    "va_status_string", "va_version",
 )
 
 
@@ -62,6 +63,10 @@ def lib() -> C.CDLL:
         C.c_int, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
     L.va_varlen_attn_bwd_stages.restype = C.c_int
     L.va_varlen_attn_bwd_stages.argtypes = L.va_varlen_attn_bwd.argtypes + [C.c_uint32]
+    L.va_collate_padding_free.restype = C.c_int
+    L.va_collate_padding_free.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int32, C.c_int32,
+                                          C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
+                                          C.c_void_p, C.c_void_p]
     L.va_status_string.restype = C.c_char_p
     L.va_status_string.argtypes = [C.c_int]
     L.va_version.restype = C.c_char_p
@@ -170,6 +175,33 @@ def pack_to_cu_seqlens(position_ids: torch.Tensor, seg: Optional[Segments] = Non
     _check("va_pack_to_cu_seqlens",
            lib().va_pack_to_cu_seqlens(position_ids.data_ptr(), it, R, T, C.byref(seg.c), _stream()))
     return seg
+
+
+def collate_padding_free(ids_padded: torch.Tensor, lengths: torch.Tensor, n_out: int,
+                         labels_padded: Optional[torch.Tensor] = None, pad_id: int = 0, out=None):
+    """Padded batch [n, Lp] + lengths [n] (int32) -> dict(input_ids, labels, position_ids: [1, n_out]
+    of the ids' dtype; example_offsets int32 [n + 1]).  Enqueues kernels only."""
+    _need_cuda(ids_padded, lengths)
+    if ids_padded.dim() != 2 or lengths.dim() != 1 or lengths.shape[0] != ids_padded.shape[0]:
+        raise ValueError("expected ids_padded [n, Lp] and lengths [n]")
+    if ids_padded.dtype not in (torch.int32, torch.int64) or lengths.dtype != torch.int32:
+        raise TypeError("ids must be int32 or int64, lengths int32")
+    if labels_padded is not None:
+        _need_cuda(labels_padded)
+        if labels_padded.shape != ids_padded.shape or labels_padded.dtype != ids_padded.dtype:
+            raise ValueError("labels_padded must match ids_padded")
+    n, Lp = ids_padded.shape
+    it = VA_I64 if ids_padded.dtype == torch.int64 else VA_I32
+    dev = ids_padded.device
+    if out is None:
+        out = {k: torch.empty((1, n_out), dtype=ids_padded.dtype, device=dev)
+               for k in ("input_ids", "labels", "position_ids")}
+        out["example_offsets"] = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    _check("va_collate_padding_free", lib().va_collate_padding_free(
+        ids_padded.data_ptr() if n else None, None if labels_padded is None else labels_padded.data_ptr(), it,
+        lengths.data_ptr() if n else None, n, Lp, n_out, int(pad_id), out["input_ids"].data_ptr(),
+        out["labels"].data_ptr(), out["position_ids"].data_ptr(), out["example_offsets"].data_ptr(), _stream()))
+    return out
 
 
 def _shapes(q, k, v, seg):

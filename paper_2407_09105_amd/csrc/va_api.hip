@@ -98,6 +98,22 @@ va_status va_pack_to_cu_seqlens(const void *position_ids, va_itype it, int32_t r
   return e == hipSuccess ? VA_OK : VA_ERR_HIP;
 }
 
+va_status va_collate_padding_free(const void *ids_padded, const void *labels_padded, va_itype it,
+                                  const int32_t *lengths, int32_t n_examples, int32_t padded_len,
+                                  int32_t n_out, int64_t pad_id, void *input_ids, void *labels,
+                                  void *position_ids, int32_t *example_offsets, void *stream) {
+  if (n_examples < 0 || padded_len <= 0 || n_out < 0) return VA_ERR_SHAPE;
+  if ((long long)n_examples * padded_len >= (1ll << 31) - 1) return VA_ERR_SHAPE;
+  if (it != VA_I32 && it != VA_I64) return VA_ERR_UNSUPPORTED;
+  if (!example_offsets) return VA_ERR_NULL;
+  if (n_examples > 0 && (!ids_padded || !lengths)) return VA_ERR_NULL;
+  if (n_out > 0 && (!input_ids || !labels || !position_ids)) return VA_ERR_NULL;
+  hipError_t e = va::launch_collate(ids_padded, labels_padded, it, lengths, n_examples, padded_len, n_out,
+                                    (long long)pad_id, input_ids, labels, position_ids, example_offsets,
+                                    (hipStream_t)stream);
+  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
+}
+
 size_t va_attn_workspace_bytes(int32_t n_tokens, int32_t hq, int32_t hkv, int32_t d, int is_bwd) {
   if (n_tokens <= 0 || hq <= 0 || hkv <= 0 || d <= 0) return 0;
   if (!is_bwd) return 0;

@@ -16,6 +16,11 @@ static inline int ceil_div(int a, int b) { return (a + b - 1) / b; }
 hipError_t launch_pack(const void *pos, va_itype it, int rows, int T, const va_segments &seg,
                        hipStream_t stream);
 
+// va_collate.hip
+hipError_t launch_collate(const void *ids, const void *labels_in, va_itype it, const int32_t *lengths,
+                          int n, int Lp, int n_out, long long pad_id, void *input_ids, void *labels,
+                          void *position_ids, int32_t *offsets, hipStream_t stream);
+
 // va_generic.hip : plain fp32-arithmetic kernels, any head_dim <= 256
 hipError_t launch_generic_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
                               const va_segments &seg, int N, int hq, int hkv, int d, va_dtype dt,

@@ -70,6 +70,28 @@ def test_pack_validation(L):
     assert L.va_pack_to_cu_seqlens(p, binding.VA_I64, 1, 16, C.byref(binding.VaSegments()), None) == 1
 
 
+def test_collate_validation(L):
+    p = 0x10000  # never dereferenced: every call below fails validation
+    f = L.va_collate_padding_free
+    ok = [p, None, binding.VA_I64, p, 4, 16, 40, 0, p, p, p, p, None]
+
+    def with_(i, v):
+        a = list(ok)
+        a[i] = v
+        return a
+
+    assert f(*with_(4, -1)) == 2            # n_examples < 0
+    assert f(*with_(5, 0)) == 2             # padded_len <= 0
+    assert f(*with_(6, -1)) == 2            # n_out < 0
+    a = with_(4, 1 << 20)
+    a[5] = 1 << 12
+    assert f(*a) == 2                       # n_examples * padded_len >= 2^31
+    assert f(*with_(2, 5)) == 3             # unknown id type
+    assert f(*with_(0, None)) == 1 and f(*with_(3, None)) == 1
+    assert f(*with_(8, None)) == 1 and f(*with_(9, None)) == 1 and f(*with_(10, None)) == 1
+    assert f(*with_(11, None)) == 1
+
+
 def test_attn_validation(L):
     seg = _bound(L)
     p = 0x20000
