@@ -81,6 +81,20 @@ def collate(ids_padded, lengths, n_out, labels_padded=None, pad_id=0):
     return out
 
 
+def rope(x, position_ids, base=10000.0, inverse=False):
+    """Rotary embedding of x [N, H, d] at positions position_ids (any shape with N entries) -> fp64."""
+    x = _f64(x)
+    N, H, d = x.shape
+    pos = np.ascontiguousarray(position_ids, dtype=np.int64).reshape(-1)
+    assert pos.shape[0] == N
+    y = np.empty_like(x)
+    rc = lib().oracle_rope(_p(x, C.c_double), _p(y, C.c_double), _p(pos, C.c_int64), C.c_int64(N), C.c_int(H),
+                           C.c_int(d), C.c_double(base), C.c_int(1 if inverse else 0))
+    if rc != 0:
+        raise RuntimeError(f"oracle_rope failed: {rc}")
+    return y
+
+
 def _dims(q, k):
     N, Hq, d = q.shape
     Nk, Hkv, dk = k.shape

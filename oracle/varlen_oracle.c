@@ -109,6 +109,38 @@ int oracle_collate(const int64_t *ids, const int64_t *labels_in, const int32_t *
     return 0;
 }
 
+/* ---- rotary position embedding ---------------------------------------- */
+
+/* The other consumer of the restarting position ids (Section 3: models that take
+ * position ids apply them to their positional encoding, so a packed example is
+ * encoded exactly as if it were alone).  Textbook rotary embedding in the
+ * "rotate-half" pairing: for a head vector x of even length d at position p,
+ * pair c in [0, d/2) is (x[c], x[c + d/2]), rotated by the angle
+ *     a = p * base^(-2c/d):   y[c]       = x[c] cos a - x[c + d/2] sin a
+ *                             y[c + d/2] = x[c + d/2] cos a + x[c] sin a
+ * inverse != 0 rotates by -a (the transpose: what the gradient needs).
+ * X, Y: [N, H, d] doubles; pos: [N].  The paper names no pairing or base: this
+ * is the one its listed decoder models use, base passed in. */
+int oracle_rope(const double *X, double *Y, const int64_t *pos, int64_t N, int H, int d,
+                double base, int inverse)
+{
+    if (!X || !Y || !pos || N < 0 || H <= 0 || d <= 0 || (d & 1) || base <= 0.0) return 1;
+    const int hd = d / 2;
+    for (int64_t t = 0; t < N; ++t)
+        for (int c = 0; c < hd; ++c) {
+            double a = (double)pos[t] * pow(base, -2.0 * (double)c / (double)d);
+            if (inverse) a = -a;
+            const double cs = cos(a), sn = sin(a);
+            for (int h = 0; h < H; ++h) {
+                const size_t o = ((size_t)t * H + h) * d;
+                const double x1 = X[o + c], x2 = X[o + c + hd];
+                Y[o + c] = x1 * cs - x2 * sn;
+                Y[o + c + hd] = x2 * cs + x1 * sn;
+            }
+        }
+    return 0;
+}
+
 /* ---- one query row ---------------------------------------------------- */
 
 /* Softmax row of token i, head h, over keys a..i of KV head g.  Fills
