@@ -158,6 +158,26 @@ def collate_timing(torch, binding, w, steps):
             "bound": "launch latency (two tiny kernels)", "position_ids_match_workload": ok}
 
 
+def rope_timing(torch, binding, w, q, steps):
+    """Rotary embedding of Q in place from the workload's position ids: HBM-bound, one read + one write."""
+    pos = torch.from_numpy(w.position_ids).cuda().reshape(-1)
+    x = q.clone()
+    for _ in range(3):
+        binding.rope_apply(x, pos, out=x)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        binding.rope_apply(x, pos, out=x)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    algo_bytes = 2 * x.numel() * x.element_size() + pos.numel() * 8
+    return {"tensor": "Q " + "x".join(str(s) for s in x.shape) + " bf16, in place", "ms": ms,
+            "algorithmic_bytes": algo_bytes, "achieved_GBs": algo_bytes / (ms * 1e-3) / 1e9,
+            "frac_hbm_peak": algo_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bound": "hbm"}
+
+
 def cpu_baseline(wl, cfg_id, heads):
     """The oracle as it stands, timed on the host cores, on a bounded sample of the workload:
     the same packed rows and lengths with fewer heads (work is exactly linear in heads)."""
@@ -291,6 +311,7 @@ def main():
             "executed_pairs_per_head": cfg.rows * T * (T + 1) // 2, "position_id_gain": nms / ms_plain,
         }
         out["collate"] = collate_timing(torch, binding, w, args.steps)
+        out["rope"] = rope_timing(torch, binding, w, q, args.steps)
     if not args.no_cpu_baseline:
         heads = args.cpu_heads or {2: 32, 3: 16, 4: 32, 5: 0}.get(cfg_id, 8)
         if heads:

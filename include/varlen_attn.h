@@ -114,6 +114,24 @@ va_status va_collate_padding_free(const void *ids_padded, const void *labels_pad
                                   int32_t n_out, int64_t pad_id, void *input_ids, void *labels,
                                   void *position_ids, int32_t *example_offsets, void *stream);
 
+/*
+ * Rotary position embedding from the same position ids (paper, Section 3: a model that accepts
+ * position ids applies them to its positional encoding, so every packed example is encoded as if
+ * it were alone).  For each token t, head h and pair c in [0, d/2):
+ *     a = position_ids[t] * theta_base^(-2c/d)
+ *     y[t,h,c]       = x[t,h,c] cos a - x[t,h,c+d/2] sin a
+ *     y[t,h,c + d/2] = x[t,h,c+d/2] cos a + x[t,h,c] sin a
+ * ("rotate-half" pairing; the paper fixes neither pairing nor base).
+ *   x, y          : device, [n_tokens, heads, d] of `dt`; y may be x (in place).  d even, <= 256.
+ *   position_ids  : device, [n_tokens] of `it` (the flattened [rows, tokens_per_row] ids).
+ *   theta_base    : <= 0 means 10000.
+ *   inverse       : non-zero rotates by -a (the transpose): d(loss)/dx from d(loss)/dy.
+ * Angles are formed and range-reduced in fp64, products in fp32; bf16 results are rounded to nearest even.
+ */
+va_status va_rope_apply(const void *x, void *y, va_dtype dt, const void *position_ids, va_itype it,
+                        int32_t n_tokens, int32_t heads, int32_t d, float theta_base, int inverse,
+                        void *stream);
+
 /* Workspace bytes for one forward (is_bwd = 0) or backward (is_bwd = 1) call (0 on bad shape). */
 size_t va_attn_workspace_bytes(int32_t n_tokens, int32_t hq, int32_t hkv, int32_t d, int is_bwd);
 

@@ -25,7 +25,7 @@ STAGE_D, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 EXPORTS = (
     "va_plan_bytes", "va_segments_bind", "va_pack_to_cu_seqlens", "va_attn_workspace_bytes",
     "va_varlen_attn_fwd", "va_varlen_attn_bwd", "va_varlen_attn_bwd_stages", "va_collate_padding_free",
-    "va_status_string", "va_version",
+    "va_rope_apply", "va_status_string", "va_version",
 )
 
 
@@ -67,6 +67,9 @@ def lib() -> C.CDLL:
     L.va_collate_padding_free.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int32, C.c_int32,
                                           C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
                                           C.c_void_p, C.c_void_p]
+    L.va_rope_apply.restype = C.c_int
+    L.va_rope_apply.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
+                                C.c_int32, C.c_float, C.c_int, C.c_void_p]
     L.va_status_string.restype = C.c_char_p
     L.va_status_string.argtypes = [C.c_int]
     L.va_version.restype = C.c_char_p
@@ -202,6 +205,26 @@ def collate_padding_free(ids_padded: torch.Tensor, lengths: torch.Tensor, n_out:
         lengths.data_ptr() if n else None, n, Lp, n_out, int(pad_id), out["input_ids"].data_ptr(),
         out["labels"].data_ptr(), out["position_ids"].data_ptr(), out["example_offsets"].data_ptr(), _stream()))
     return out
+
+
+def rope_apply(x: torch.Tensor, position_ids: torch.Tensor, theta_base: float = 10000.0, inverse: bool = False,
+               out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Rotary embedding of x [N, H, d] (float32 or bfloat16) at position_ids (N entries, int32/int64).
+    out may be x (in place).  Enqueues one kernel."""
+    _need_cuda(x, position_ids)
+    if x.dim() != 3 or position_ids.numel() != x.shape[0]:
+        raise ValueError("expected x [N, H, d] and N position ids")
+    if position_ids.dtype not in (torch.int32, torch.int64):
+        raise TypeError("position_ids must be int32 or int64")
+    y = torch.empty_like(x) if out is None else out
+    if y.shape != x.shape or y.dtype != x.dtype:
+        raise ValueError("out must match x")
+    _need_cuda(y)
+    N, H, d = x.shape
+    _check("va_rope_apply", lib().va_rope_apply(
+        x.data_ptr(), y.data_ptr(), _dt(x), position_ids.data_ptr(),
+        VA_I64 if position_ids.dtype == torch.int64 else VA_I32, N, H, d, float(theta_base), int(inverse), _stream()))
+    return y
 
 
 def _shapes(q, k, v, seg):

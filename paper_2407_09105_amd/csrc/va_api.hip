@@ -114,6 +114,20 @@ va_status va_collate_padding_free(const void *ids_padded, const void *labels_pad
   return e == hipSuccess ? VA_OK : VA_ERR_HIP;
 }
 
+va_status va_rope_apply(const void *x, void *y, va_dtype dt, const void *position_ids, va_itype it,
+                        int32_t n_tokens, int32_t heads, int32_t d, float theta_base, int inverse,
+                        void *stream) {
+  if (n_tokens < 0 || heads <= 0 || d <= 0 || (d & 1)) return VA_ERR_SHAPE;
+  if (dt != VA_F32 && dt != VA_BF16) return VA_ERR_UNSUPPORTED;
+  if (it != VA_I32 && it != VA_I64) return VA_ERR_UNSUPPORTED;
+  if (d > 256) return VA_ERR_UNSUPPORTED;
+  if (n_tokens > 0 && (!x || !y || !position_ids)) return VA_ERR_NULL;
+  const double base = theta_base > 0.f ? (double)theta_base : 10000.0;
+  hipError_t e = va::launch_rope(x, y, dt, position_ids, it, n_tokens, heads, d, base, inverse != 0,
+                                 (hipStream_t)stream);
+  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
+}
+
 size_t va_attn_workspace_bytes(int32_t n_tokens, int32_t hq, int32_t hkv, int32_t d, int is_bwd) {
   if (n_tokens <= 0 || hq <= 0 || hkv <= 0 || d <= 0) return 0;
   if (!is_bwd) return 0;

@@ -92,6 +92,23 @@ def test_collate_validation(L):
     assert f(*with_(11, None)) == 1
 
 
+def test_rope_validation(L):
+    p = 0x10000  # never dereferenced: every call below fails validation
+    f = L.va_rope_apply
+    ok = [p, p, binding.VA_BF16, p, binding.VA_I64, 64, 4, 128, 0.0, 0, None]
+
+    def with_(i, v):
+        a = list(ok)
+        a[i] = v
+        return a
+
+    assert f(*with_(5, -1)) == 2 and f(*with_(6, 0)) == 2
+    assert f(*with_(7, 0)) == 2 and f(*with_(7, 127)) == 2      # head_dim must be even
+    assert f(*with_(7, 258)) == 3
+    assert f(*with_(2, 9)) == 3 and f(*with_(4, 9)) == 3
+    assert f(*with_(0, None)) == 1 and f(*with_(1, None)) == 1 and f(*with_(3, None)) == 1
+
+
 def test_attn_validation(L):
     seg = _bound(L)
     p = 0x20000
