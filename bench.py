@@ -178,6 +178,45 @@ def rope_timing(torch, binding, w, q, steps):
             "frac_hbm_peak": algo_bytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "bound": "hbm"}
 
 
+def measured_peaks(torch, binding):
+    """What this GPU sustains: a matrix-instruction-only loop and a plain 256 MiB device copy."""
+    sink = torch.zeros(64, dtype=torch.float32, device="cuda")
+    binding.probe_mfma(sink, 2000)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    fl = binding.probe_mfma(sink, 20000)
+    e1.record()
+    torch.cuda.synchronize()
+    mfma = fl / (e0.elapsed_time(e1) * 1e-3) / 1e12
+    src = torch.empty(64 * 1024 * 1024, dtype=torch.float32, device="cuda").fill_(1.0)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    copy = 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return {"mfma_bf16_TFLOPs": mfma, "device_copy_GBs": copy,
+            "note": "bf16 32x32x16 matrix instructions only, 2 waves per SIMD; 256 MiB device-to-device copy (read + write bytes)"}
+
+
+def cold_cache_ms(torch, binding, w, q, k, v, do, steps, copies=3):
+    """The same step cycling through `copies` independent sets of inputs and outputs (each ~0.5 GB on
+    config 2), so that no step finds its tensors in the 256 MB last-level cache."""
+    runs = [GpuRun(torch, binding, w.position_ids, q.clone(), k.clone(), v.clone(), do.clone()) for _ in range(copies)]
+    for r in runs:
+        r.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        runs[s % copies].step()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
 def cpu_baseline(wl, cfg_id, heads):
     """The oracle as it stands, timed on the host cores, on a bounded sample of the workload:
     the same packed rows and lengths with fewer heads (work is exactly linear in heads)."""
@@ -300,6 +339,11 @@ def main():
             "tokens_per_s": cfg.n_tokens / (pms * 1e-3), "packing_gain": pms / ms_plain,
         }
         del prun
+    out["measured_peaks"] = measured_peaks(torch, binding)
+    out["frac_measured_mfma_peak"] = value / out["measured_peaks"]["mfma_bf16_TFLOPs"]
+    cold = cold_cache_ms(torch, binding, w, q, k, v, do, args.steps)
+    out["cold_cache"] = {"ms_per_step": cold, "value": useful / (cold * 1e-3) / 1e12, "unit": "TFLOP/s (useful)",
+                         "note": "3 input/output sets cycled; `value` above re-uses one set (inputs partly cache-resident)"}
     if not args.no_extras:
         nrun = no_posid_run(torch, binding, w, q, k, v, do)
         nms, _ = timed(torch, nrun, max(5, args.steps // 2), 3, with_events=False)

@@ -186,6 +186,15 @@ va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K
                                     va_dtype dt, float softmax_scale, void *workspace,
                                     size_t workspace_bytes, void *stream, uint32_t stages);
 
+/*
+ * Measurement aid (no part of the method): enqueue a kernel that issues nothing but bf16
+ * 32x32x16 matrix instructions on every SIMD, `iters` (1 .. 2^24) rounds of 16 per wave.  The caller
+ * times it with events on `stream`; *flops (host, may be NULL) receives the floating-point
+ * operations the launch performs.  flops / time is the matrix rate this GPU sustains, reported by
+ * the benchmark beside the published peak.  sink: device, >= 64 floats, normally left untouched.
+ */
+va_status va_probe_mfma(float *sink, int32_t iters, double *flops /* host, out */, void *stream);
+
 /* Static string for a status code. */
 const char *va_status_string(va_status s);
 

@@ -25,7 +25,7 @@ STAGE_D, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 EXPORTS = (
     "va_plan_bytes", "va_segments_bind", "va_pack_to_cu_seqlens", "va_attn_workspace_bytes",
     "va_varlen_attn_fwd", "va_varlen_attn_bwd", "va_varlen_attn_bwd_stages", "va_collate_padding_free",
-    "va_rope_apply", "va_status_string", "va_version",
+    "va_rope_apply", "va_probe_mfma", "va_status_string", "va_version",
 )
 
 
@@ -70,6 +70,8 @@ def lib() -> C.CDLL:
     L.va_rope_apply.restype = C.c_int
     L.va_rope_apply.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
                                 C.c_int32, C.c_float, C.c_int, C.c_void_p]
+    L.va_probe_mfma.restype = C.c_int
+    L.va_probe_mfma.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
     L.va_status_string.restype = C.c_char_p
     L.va_status_string.argtypes = [C.c_int]
     L.va_version.restype = C.c_char_p
@@ -225,6 +227,16 @@ def rope_apply(x: torch.Tensor, position_ids: torch.Tensor, theta_base: float = 
         x.data_ptr(), y.data_ptr(), _dt(x), position_ids.data_ptr(),
         VA_I64 if position_ids.dtype == torch.int64 else VA_I32, N, H, d, float(theta_base), int(inverse), _stream()))
     return y
+
+
+def probe_mfma(sink: torch.Tensor, iters: int) -> float:
+    """Enqueue the matrix-instruction-only kernel; returns the FLOPs it performs (time it with events)."""
+    _need_cuda(sink)
+    if sink.dtype != torch.float32 or sink.numel() < 64:
+        raise ValueError("sink must hold at least 64 float32")
+    fl = C.c_double(0.0)
+    _check("va_probe_mfma", lib().va_probe_mfma(sink.data_ptr(), int(iters), C.byref(fl), _stream()))
+    return fl.value
 
 
 def _shapes(q, k, v, seg):

@@ -128,6 +128,13 @@ va_status va_rope_apply(const void *x, void *y, va_dtype dt, const void *positio
   return e == hipSuccess ? VA_OK : VA_ERR_HIP;
 }
 
+va_status va_probe_mfma(float *sink, int32_t iters, double *flops, void *stream) {
+  if (!sink) return VA_ERR_NULL;
+  if (iters <= 0 || iters > (1 << 24)) return VA_ERR_SHAPE;
+  hipError_t e = va::launch_mfma_probe(sink, iters, flops, (hipStream_t)stream);
+  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
+}
+
 size_t va_attn_workspace_bytes(int32_t n_tokens, int32_t hq, int32_t hkv, int32_t d, int is_bwd) {
   if (n_tokens <= 0 || hq <= 0 || hkv <= 0 || d <= 0) return 0;
   if (!is_bwd) return 0;
