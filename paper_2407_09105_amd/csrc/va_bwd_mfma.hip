@@ -11,7 +11,7 @@
 //                      Lane owns a query row: S^T = K Q^T, dP^T = V dO^T, dQ^T += K^T dS^T.
 //   dkdv_mfma_kernel : workgroup = (128-key tile, KV head); streams Q/dO blocks of 64 rows of every
 //                      query head of the group.  Lane owns a key row: S = Q K^T, dP = dO V^T,
-//                      dV^T += dO^T P, dK^T += Q^T dS.
+//                      dV^T += dO^T P, dK^T += Q^T dS; the dV and the dK halves run on different waves.
 // In both, the streamed index lies on the accumulator's register axis and feeds the last
 // contraction as a B operand straight from registers (see va_mfma_common.h).
 #include "va_internal.h"
@@ -26,7 +26,6 @@ constexpr int kBS = 64;              // streamed rows per LDS block
 constexpr int kBlk = kBS * kD;       // elements of one swizzled [64][128] LDS block (16 KB)
 constexpr float kLog2e = 1.4426950408889634f;
 
-typedef BlockCopy<kBS, 256> Copy;  // 4 x 16 B per thread and block
 
 // ---------------------------------------------------------------------------------------------
 template <bool kF32Out>
@@ -164,82 +163,40 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   store_transposed_tile<kF32Out>(acc, scale, stage, dQ, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h);
 }
 
-// One 32-query sub-block of the dK/dV kernel for this wave's 32 keys.  All LDS fragments of a phase
-// are requested before the MFMAs that consume them, and the transposed fragments of the second
-// phase are requested before the exp / dS arithmetic, so LDS latency overlaps matrix and vector work.
-__device__ __forceinline__ void dkdv_subblock(bool need_mask, f32x16 (&dk_acc)[4], f32x16 (&dv_acc)[4], const bf16x8 (&kf)[8],
-                                              const bf16x8 (&vf)[8], const uint16_t *Qs, const uint16_t *Gs,
-                                              const float *lse_s, const float *dl_s, int row0, uint32_t row_lane,
-                                              const uint32_t (&tr_lane)[2], int half, int il, int j_abs, int se_j,
-                                              float scale_log2) {
-  // the accumulators start from the per-query constants: S from -LSE / scale, dP from -D
-  f32x16 s, dp;
-#pragma unroll
-  for (int q4 = 0; q4 < 4; ++q4) {
-    const f32x4 l = *(const f32x4 *)(lse_s + row0 + q4 * 8 + half * 4);
-    const f32x4 d = *(const f32x4 *)(dl_s + row0 + q4 * 8 + half * 4);
-#pragma unroll
-    for (int b = 0; b < 4; ++b) { s[q4 * 4 + b] = l[b]; dp[q4 * 4 + b] = d[b]; }
-  }
-  bf16x8 aq[8], ag[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    aq[ks] = swz_read_row(Qs, row_lane, ks, row0);
-    ag[ks] = swz_read_row(Gs, row_lane, ks, row0);
-  }
-  __builtin_amdgcn_sched_barrier(0);  // keep every read above in flight before the first MFMA
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) {
-    s = mfma32(aq[ks], kf[ks], s);     // S - LSE / scale  = Q K^T - LSE / scale
-    dp = mfma32(ag[ks], vf[ks], dp);   // dP - D           = dO V^T - D
-  }
-  bf16x8 tq[2][4], tg[2][4];
-#pragma unroll
-  for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-    for (int cb = 0; cb < 4; ++cb) {
-      tg[s2][cb] = swz_read_tr(Gs, tr_lane, cb, row0 + s2 * 16);
-      tq[s2][cb] = swz_read_tr(Qs, tr_lane, cb, row0 + s2 * 16);
-    }
-  __builtin_amdgcn_sched_barrier(0);  // transposed fragments land while the arithmetic below runs
-#pragma unroll
-  for (int v = 0; v < 16; ++v) s[v] = __builtin_amdgcn_exp2f(s[v] * scale_log2);  // P
-  if (need_mask) {  // wave-uniform; touches only the probabilities
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int i = il + acc_row(v, half);
-      if (i < j_abs || i >= se_j) s[v] = 0.f;
-    }
-  }
-#pragma unroll
-  for (int v = 0; v < 16; ++v) dp[v] *= s[v];  // dS
-#pragma unroll
-  for (int s2 = 0; s2 < 2; ++s2) {
-    const bf16x8 pf = pack_bf16x8(s, 8 * s2);
-    const bf16x8 df = pack_bf16x8(dp, 8 * s2);
-#pragma unroll
-    for (int cb = 0; cb < 4; ++cb) {
-      dv_acc[cb] = mfma32(tg[s2][cb], pf, dv_acc[cb]);  // dV^T += dO^T P
-      dk_acc[cb] = mfma32(tq[s2][cb], df, dk_acc[cb]);  // dK^T += Q^T dS
-    }
-  }
+// ---------------------------------------------------------------------------------------------
+// dK/dV with the two gradients on different waves.  Workgroup = 8 waves = (128-key tile, KV head);
+// waves 0..3 ("V side") and 4..7 ("K side") each own 32 keys, wave w and w + 4 the same ones, and
+// share a SIMD.  Per 32-query sub-block:
+//   V side: S = Q K^T (on -LSE / scale), P = exp2, mask; hands P (bf16) to its partner through LDS;
+//           dV^T += dO^T P.
+//   K side: dP = dO V^T (on -D); after the hand-over dS = P * dP; dK^T += Q^T dS.
+// Each wave holds one accumulator tile and one operand tile (about 200 registers), so two waves fit
+// per SIMD and one wave's exp / convert / LDS work overlaps the other's matrix instructions.
+constexpr int kDkdvThreads = 512;
+
+__device__ __forceinline__ void lds_barrier() {  // LDS traffic of this wave done, then workgroup barrier
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// ---------------------------------------------------------------------------------------------
 template <bool kF32Out>
-__global__ void __launch_bounds__(256, 1)
+__global__ void __launch_bounds__(kDkdvThreads, 1)
 dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
-                 const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
-                 const float *__restrict__ LSE, const float *__restrict__ delta, void *__restrict__ dK,
-                 void *__restrict__ dV, const int32_t *__restrict__ seg_end,
-                 const int32_t *__restrict__ kv_tile_order, int N, int T, int tiles_per_row, int hq,
-                 int hkv, float scale_log2, float scale) {
-  // two stages of {Q block, dO block (swizzled), -LSE / scale [64], -D [64]}
-  constexpr int kStage = 2 * kBlk + 4 * kBS;  // elements (floats take two)
-  __shared__ __attribute__((aligned(16))) uint16_t lds[2 * kStage];
-  static_assert(2 * kStage * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit");
+                  const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+                  const float *__restrict__ LSE, const float *__restrict__ delta, void *__restrict__ dK,
+                  void *__restrict__ dV, const int32_t *__restrict__ seg_end,
+                  const int32_t *__restrict__ kv_tile_order, int N, int T, int tiles_per_row, int hq,
+                  int hkv, float scale_log2, float scale) {
+  // two stages of {Q block, dO block (swizzled), -LSE / scale [64], -D [64]}; reused as the staging
+  // area of the result stores (8 waves)
+  constexpr int kStage = 2 * kBlk + 4 * kBS;
+  constexpr int kStagesElems = 8 * kStageFloatsPerWave * 2 > 2 * kStage ? 8 * kStageFloatsPerWave * 2 : 2 * kStage;
+  __shared__ __attribute__((aligned(16))) uint16_t stages[kStagesElems];
+  // P hand-over: [key group 4][parity 2][part 2][lane 64] x 16 B
+  __shared__ __attribute__((aligned(16))) u32x4 exch[4 * 2 * 2 * 64];
 
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
+  const int kg = wave & 3;
+  const bool k_side = wave >= 4;
   const int l32 = lane & 31, half = lane >> 5;
   const int tile = uniform(kv_tile_order[blockIdx.x / (hkv * kSub)]);
   const int sub = (blockIdx.x / hkv) % kSub;
@@ -250,45 +207,48 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const int t0 = r * T + m * VA_TILE + sub * kBT;
   if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
   const int t_last = min(t0 + kBT, row_end) - 1;
-  const int ib_lo = t0 / kBS;  // first query block that can see a key of this tile
+  const int ib_lo = t0 / kBS;
 
   const size_t row_bytes = (size_t)hq * kD * 2;
   const size_t base_off = (size_t)ib_lo * kBS * row_bytes;
   const size_t total = (size_t)N * row_bytes;
   const buffer_t qbuf = make_buffer((const char *)Q + base_off, total - base_off);
   const buffer_t gbuf = make_buffer((const char *)dO + base_off, total - base_off);
-  // HBM -> LDS copy of a 64-row Q / dO block by the load unit (see the forward kernel)
-  const int dma_row = wave * 4 + (lane >> 4);
+  // HBM -> LDS copy of a 64-row block: 16 transfers of 1 KB (4 rows) per tensor, two per wave
+  const int dma_row = wave * 4 + (lane >> 4);  // and 32 rows further for the second transfer (same swizzle)
   const uint32_t dma_off = (uint32_t)(dma_row * row_bytes + (((lane & 15) ^ swz(dma_row)) << 4));
   const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
-  const uint32_t p_bytes = (uint32_t)(16 * row_bytes);
+  const uint32_t p_bytes = (uint32_t)(32 * row_bytes);
   typedef __attribute__((address_space(3))) void *lds_void;
   const int stat_row = threadIdx.x & (kBS - 1);
-  const bool stat_is_lse = (threadIdx.x & kBS) == 0;  // threads 0..63 (and 128..191): LSE; others: D
+  const bool stat_is_lse = (threadIdx.x & kBS) == 0;
   const float *stat_src = stat_is_lse ? LSE : delta;
   const float stat_mul = stat_is_lse ? -1.f / scale : -1.f;
-  float rstat;
-  // Q, dO blocks (query head g * G + hh, block ib) -> stage at dst; LSE / D value -> rstat
+  float rstat = 0.f;
   auto copy_block = [&](uint16_t *dst, int hh, int ib) {
-    const int i = min(ib * kBS + stat_row, N - 1);
-    rstat = stat_src[(size_t)(g * G + hh) * N + i];
+    if (threadIdx.x < 2 * kBS) {
+      const int i = min(ib * kBS + stat_row, N - 1);
+      rstat = stat_src[(size_t)(g * G + hh) * N + i];
+    }
     const uint32_t off = dma_off + (uint32_t)(ib - ib_lo) * blk_bytes + (uint32_t)((g * G + hh) * kD * 2);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(qbuf, (lds_void)(dst + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(gbuf, (lds_void)(dst + kBlk + (4 * p + wave) * 512), 16,
+    for (int p = 0; p < 2; ++p) {
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(qbuf, (lds_void)(dst + (8 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(gbuf, (lds_void)(dst + kBlk + (8 * p + wave) * 512), 16,
                                                off + p * p_bytes, 0, 0, 0);
     }
   };
-  // the first block needs nothing but the tile: its copy starts before the example bounds arrive
-  uint16_t *S0 = lds, *S1 = lds + kStage;
-  copy_block(S0, 0, ib_lo);
+  auto put_stats = [&](uint16_t *dst) {
+    if (threadIdx.x < 2 * kBS) ((float *)(dst + 2 * kBlk))[threadIdx.x] = rstat * stat_mul;
+  };
+  uint16_t *S0 = stages, *S1 = stages + kStage;
+  copy_block(S0, 0, ib_lo);  // needs nothing but the tile: in flight while the bounds arrive
 
-  // query blocks end with the example holding the tile's last key
   const int ib_hi = (uniform(seg_end[t_last]) - 1) / kBS;
   const int nb = ib_hi - ib_lo + 1;
+  const int n_it = nb * G;
 
-  const int jw0 = t0 + wave * 32;
+  const int jw0 = t0 + kg * 32;
   const int jw1 = min(jw0 + 31, t_last);
   const bool wave_ok = jw0 <= t_last;
   const bool wave_full = jw0 + 31 <= t_last;
@@ -297,73 +257,109 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const int j_abs = jw0 + l32;
   const bool row_ok = j_abs <= t_last;
   const int j_ld = min(j_abs, t_last);
-  const int se_j = row_ok ? seg_end[j_ld] : 0;  // queries j_abs <= i < se_j see key j_abs
+  const int se_j = row_ok ? seg_end[j_ld] : 0;
 
-  bf16x8 kf[8], vf[8];  // K and V rows of this lane: B operands
+  bf16x8 rf[8];  // this lane's key row: K (V side computes S) or V (K side computes dP)
   {
+    const uint16_t *src = k_side ? V : K;
     const size_t off = ((size_t)j_ld * hkv + g) * kD + half * 8;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      kf[ks] = as_bf16x8(*(const u32x4 *)(K + off + ks * 16));
-      vf[ks] = as_bf16x8(*(const u32x4 *)(V + off + ks * 16));
-    }
+    for (int ks = 0; ks < 8; ++ks) rf[ks] = as_bf16x8(*(const u32x4 *)(src + off + ks * 16));
   }
-
-  f32x16 dk_acc[4], dv_acc[4];
+  f32x16 acc[4];
 #pragma unroll
   for (int cb = 0; cb < 4; ++cb)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) { dk_acc[cb][v] = 0.f; dv_acc[cb][v] = 0.f; }
+    for (int v = 0; v < 16; ++v) acc[cb][v] = 0.f;
 
   const uint32_t row_lane = swz_row_lane_off(lane);
   uint32_t tr_lane[2];
   swz_tr_lane_off(lane, tr_lane);
+  u32x4 *const ex = exch + kg * 256 + lane;  // + parity * 128 + part * 64
 
-  // iteration `it` streams query block ib_lo + it % nb of query head g * G + it / nb
-  const int n_it = nb * G;
-  auto put_stats = [&](uint16_t *dst) {  // [64] -LSE / scale, [64] -D behind the two blocks
-    if (threadIdx.x < 2 * kBS) ((float *)(dst + 2 * kBlk))[threadIdx.x] = rstat * stat_mul;
-  };
-
-  // One iteration: start the copy of the next block into the other stage (last read before the
-  // previous barrier), consume the current one, publish the next with the barrier at the end.
-  int ib_cur = ib_lo, ib_nxt = ib_lo, hh_nxt = 0;  // block being consumed; block / head being copied
+  int ib_cur = ib_lo, ib_nxt = ib_lo, hh_nxt = 0, par = 0;
   auto iteration = [&](int it, const uint16_t *__restrict__ cur, uint16_t *__restrict__ nxt) {
     const bool more = it + 1 < n_it;  // workgroup-uniform
     if (++ib_nxt > ib_hi) { ib_nxt = ib_lo; ++hh_nxt; }
     if (more) copy_block(nxt, hh_nxt, ib_nxt);
-    const uint16_t *Qs = cur, *Gs = cur + kBlk;
-    const float *lse_s = (const float *)(cur + 2 * kBlk), *dl_s = lse_s + kBS;
+    const uint16_t *Xs = cur + (k_side ? kBlk : 0);   // rows of S's / dP's left operand: Q or dO
+    const uint16_t *Ys = cur + (k_side ? 0 : kBlk);   // transposed operand of the second product: Q^T or dO^T
+    const float *st = (const float *)(cur + 2 * kBlk) + (k_side ? kBS : 0);  // -LSE / scale or -D
     const int i0 = ib_cur * kBS;
     ib_cur = ib_nxt;
-    if (wave_ok && i0 + kBS - 1 >= jw0 && i0 < se_max) {  // wave-uniform
-#pragma unroll 1  // one code instance per stage: the accumulators keep their registers
-      for (int sb = 0; sb < 2; ++sb) {
-        const int il = i0 + sb * 32;
-        if (il + 31 < jw0 || il >= se_max) continue;  // wave-uniform
-        const bool interior = wave_full && il >= jw1 && il + 31 < se_min;
-        dkdv_subblock(!interior, dk_acc, dv_acc, kf, vf, Qs, Gs, lse_s, dl_s, sb * 32, row_lane, tr_lane, half, il,
-                      j_abs, se_j, scale_log2);
+#pragma unroll 1
+    for (int sb = 0; sb < 2; ++sb) {
+      const int il = i0 + sb * 32, row0 = sb * 32;
+      const bool active = wave_ok && il + 31 >= jw0 && il < se_max;  // wave-uniform, same for both sides
+      f32x16 x;
+      bf16x8 ty[2][4];
+      if (active) {
+#pragma unroll
+        for (int q4 = 0; q4 < 4; ++q4) {
+          const f32x4 c = *(const f32x4 *)(st + row0 + q4 * 8 + half * 4);
+#pragma unroll
+          for (int b = 0; b < 4; ++b) x[q4 * 4 + b] = c[b];
+        }
+        bf16x8 ax[8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) ax[ks] = swz_read_row(Xs, row_lane, ks, row0);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) x = mfma32(ax[ks], rf[ks], x);  // S - LSE / scale, or dP - D
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+          for (int cb = 0; cb < 4; ++cb) ty[s2][cb] = swz_read_tr(Ys, tr_lane, cb, row0 + s2 * 16);
+        if (!k_side) {
+#pragma unroll
+          for (int v = 0; v < 16; ++v) x[v] = __builtin_amdgcn_exp2f(x[v] * scale_log2);  // P
+          const bool interior = wave_full && il >= jw1 && il + 31 < se_min;
+          if (!interior) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+              const int i = il + acc_row(v, half);
+              if (i < j_abs || i >= se_j) x[v] = 0.f;
+            }
+          }
+          ex[par * 128] = __builtin_bit_cast(u32x4, pack_bf16x8(x, 0));
+          ex[par * 128 + 64] = __builtin_bit_cast(u32x4, pack_bf16x8(x, 8));
+        }
       }
+      lds_barrier();  // P of this sub-block is in LDS
+      if (active) {
+        bf16x8 f0, f1;
+        if (k_side) {
+          const bf16x8 p0 = as_bf16x8(ex[par * 128]), p1 = as_bf16x8(ex[par * 128 + 64]);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) { x[e] *= (float)p0[e]; x[8 + e] *= (float)p1[e]; }  // dS
+        }
+        f0 = pack_bf16x8(x, 0);
+        f1 = pack_bf16x8(x, 8);
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) acc[cb] = mfma32(ty[0][cb], f0, acc[cb]);  // dV^T += dO^T P, dK^T += Q^T dS
+#pragma unroll
+        for (int cb = 0; cb < 4; ++cb) acc[cb] = mfma32(ty[1][cb], f1, acc[cb]);
+      }
+      par ^= 1;
     }
     if (more) put_stats(nxt);
-    __syncthreads();
+    wait_all_loads();
+    lds_barrier();  // next block published; every read of this stage is done
   };
 
   put_stats(S0);
-  // every load issued so far (K/V fragments included) lands here: inside the loop only the block
-  // copies are in flight, and nothing but the barrier waits for them
   wait_all_loads();
-  __syncthreads();
+  lds_barrier();
   for (int it = 0; it < n_it; it += 2) {  // bounds are workgroup-uniform: barriers stay aligned
     iteration(it, S0, S1);
     if (it + 1 < n_it) iteration(it + 1, S1, S0);
   }
 
-  float *stage = (float *)lds + wave * kStageFloatsPerWave;
+  float *stage = (float *)stages + wave * kStageFloatsPerWave;
   const int nrows = wave_ok ? jw1 - jw0 + 1 : 0;
-  store_transposed_tile<kF32Out>(dk_acc, scale, stage, dK, jw0, nrows, hkv, g);
-  store_transposed_tile<kF32Out>(dv_acc, 1.f, stage, dV, jw0, nrows, hkv, g);
+  if (k_side)
+    store_transposed_tile<kF32Out>(acc, scale, stage, dK, jw0, nrows, hkv, g);
+  else
+    store_transposed_tile<kF32Out>(acc, 1.f, stage, dV, jw0, nrows, hkv, g);
 }
 
 }  // namespace
@@ -382,16 +378,16 @@ hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const v
   const unsigned gq = (unsigned)(ntiles * hq), gkv = (unsigned)(ntiles * hkv);
   const bool do_kv = stages & VA_STAGE_DKDV, do_q = stages & VA_STAGE_DQ;
   if (grad_dt == VA_F32) {
-    if (do_kv) dkdv_mfma_kernel<true><<<gkv, 256, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
-                                                    seg.kv_tile_order, N, T, tiles_per_row, hq, hkv,
-                                                    scale_log2, scale);
+    if (do_kv) dkdv_mfma_kernel<true><<<gkv, kDkdvThreads, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
+                                                              seg.kv_tile_order, N, T, tiles_per_row, hq, hkv,
+                                                              scale_log2, scale);
     if (do_q) dq_mfma_kernel<true><<<gq, 256, 0, stream>>>(g, q, k, v, LSE, delta, dQ, seg.seg_start,
                                                  seg.q_tile_order, N, T, tiles_per_row, hq, hkv,
                                                  scale_log2, scale);
   } else {
-    if (do_kv) dkdv_mfma_kernel<false><<<gkv, 256, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
-                                                     seg.kv_tile_order, N, T, tiles_per_row, hq, hkv,
-                                                     scale_log2, scale);
+    if (do_kv) dkdv_mfma_kernel<false><<<gkv, kDkdvThreads, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
+                                                               seg.kv_tile_order, N, T, tiles_per_row, hq, hkv,
+                                                               scale_log2, scale);
     if (do_q) dq_mfma_kernel<false><<<gq, 256, 0, stream>>>(g, q, k, v, LSE, delta, dQ, seg.seg_start,
                                                   seg.q_tile_order, N, T, tiles_per_row, hq, hkv,
                                                   scale_log2, scale);
