@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the no-position-id and collator timings")
+    ap.add_argument("--packers", action="store_true",
+                    help="also time the step on packs made by the paper's samplers from one example pool")
     ap.add_argument("--cpu-heads", type=int, default=0, help="query heads in the CPU-oracle sample (0 = auto)")
     return ap.parse_args()
 
@@ -217,6 +219,37 @@ def cold_cache_ms(torch, binding, w, q, k, v, do, steps, copies=3):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def packer_runs(torch, binding, wl, cfg, seed, steps):
+    """One pool of examples drawn from the workload's length law (about 4x the workload's tokens),
+    packed into rows of the workload's row length by each sampler of Table 1; the same step on each
+    pack.  Useful FLOPs and tokens count the real examples only (a row's unused tail is one pad
+    pseudo-example: executed, not counted)."""
+    from paper_2407_09105_amd import packers as pk
+    rng = np.random.default_rng(seed + 7)
+    T = cfg.tokens_per_row
+    pool, tokens = [], 0
+    while tokens < 4 * cfg.n_tokens:
+        L = min(wl._draw_len(cfg, rng), T)
+        pool.append(L)
+        tokens += L
+    out = {"pool": {"examples": len(pool), "tokens": tokens, "row_tokens": T}}
+    g = torch.Generator(device="cuda"); g.manual_seed(11)
+    for name, fn in pk.PACKERS.items():
+        rows = fn(pool, T)
+        pos = pk.position_ids(rows, T)
+        N = pos.size
+        mk = lambda h: torch.randn((N, h, cfg.d), device="cuda", generator=g, dtype=torch.float32).to(torch.bfloat16)
+        run = GpuRun(torch, binding, pos, mk(cfg.hq), mk(cfg.hkv), mk(cfg.hkv), mk(cfg.hq))
+        ms, _ = timed(torch, run, steps, 3, with_events=False)
+        pairs = sum(L * (L + 1) // 2 for r in rows for _, L in r)
+        fl = sum(flops(cfg, pairs))
+        out[name] = {"rows": len(rows), "fill": pk.efficiency(rows, T), "ms_per_step": ms,
+                     "value": fl / (ms * 1e-3) / 1e12, "unit": "TFLOP/s (useful)",
+                     "tokens_per_s": sum(L for r in rows for _, L in r) / (ms * 1e-3)}
+        del run
+    return out
+
+
 def cpu_baseline(wl, cfg_id, heads):
     """The oracle as it stands, timed on the host cores, on a bounded sample of the workload:
     the same packed rows and lengths with fewer heads (work is exactly linear in heads)."""
@@ -356,6 +389,8 @@ def main():
         }
         out["collate"] = collate_timing(torch, binding, w, args.steps)
         out["rope"] = rope_timing(torch, binding, w, q, args.steps)
+    if args.packers:
+        out["packers"] = packer_runs(torch, binding, wl, cfg, w.seed, max(5, args.steps // 4))
     if not args.no_cpu_baseline:
         heads = args.cpu_heads or {2: 32, 3: 16, 4: 32, 5: 0}.get(cfg_id, 8)
         if heads:
