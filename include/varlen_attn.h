@@ -41,13 +41,13 @@ typedef enum {
   VA_OK = 0,
   VA_ERR_NULL = 1,        /* a required pointer is NULL                                    */
   VA_ERR_SHAPE = 2,       /* rows/tokens/heads/head_dim <= 0, N >= 2^31, Hq % Hkv != 0      */
-  VA_ERR_UNSUPPORTED = 3, /* unknown dtype / id type, head_dim > 256, Hq > 65535, or (bf16, d = 128)
-                             (tokens_per_row + 256) * Hq * 256 >= 2^32                      */
+  VA_ERR_UNSUPPORTED = 3, /* unknown dtype / id type / gradient type, head_dim > 256, Hq > 65535, or
+                             (MFMA path) (tokens_per_row + 256) * Hq * d * 2 >= 2^32         */
   VA_ERR_WORKSPACE = 4,   /* plan buffer or workspace smaller than the *_bytes() query says */
   VA_ERR_HIP = 5          /* a launch failed (hipGetLastError after the launch)             */
 } va_status;
 
-typedef enum { VA_F32 = 0, VA_BF16 = 1 } va_dtype;  /* element type of Q/K/V/O/dO and of the gradients */
+typedef enum { VA_F32 = 0, VA_BF16 = 1, VA_F16 = 2 } va_dtype; /* element type of Q/K/V/O/dO and of the gradients */
 typedef enum { VA_I32 = 0, VA_I64 = 1 } va_itype;   /* element type of position_ids                     */
 
 /* The tile schedule is expressed in tiles of this many consecutive tokens of a packed row. */
@@ -142,8 +142,10 @@ size_t va_attn_workspace_bytes(int32_t n_tokens, int32_t hq, int32_t hkv, int32_
  * (the varlen attention routine the paper's Section 3 hands cu_seqlens to; the mask is
  * Table 1's "correct cross-attention").  Only key tiles that intersect an example's
  * causal triangle are visited.
- *   dt            : element type of Q, K, V, O.  VA_BF16 with d == 128 runs the MFMA kernels;
- *                   other (dt, d <= 256) combinations run a plain fp32-arithmetic kernel.
+ *   dt            : element type of Q, K, V, O.  VA_BF16 and VA_F16 with d a multiple of 8 up to 128
+ *                   run the MFMA kernels (unrolled for d = 64, 96, 128; a smaller d is padded with
+ *                   zero columns on the fly); other (dt, d <= 256) combinations run a plain
+ *                   fp32-arithmetic kernel.
  *   softmax_scale : <= 0 means 1 / sqrt(d).
  *   workspace     : >= va_attn_workspace_bytes(..., 0) bytes (may be NULL when that is 0).
  */
@@ -159,7 +161,8 @@ va_status va_varlen_attn_fwd(const void *Q, const void *K, const void *V, void *
  *     dK_j = scale * sum_{i >= j} dS_ij q_i,   dV_j = sum_{i >= j} P_ij dO_i
  * with dK, dV also summed over the Hq / Hkv query heads of a KV head.  Same mask, same
  * skipped tiles.  Results are deterministic (no atomics).
- *   grad_dt   : element type of dQ, dK, dV (VA_F32 or VA_BF16), independent of dt.
+ *   grad_dt   : element type of dQ, dK, dV: VA_F32, or the 16-bit type of the inputs (VA_BF16 also
+ *               with fp32 inputs); other pairs: VA_ERR_UNSUPPORTED.
  *   workspace : >= va_attn_workspace_bytes(..., 1) bytes (holds D, [Hq, N] float).
  */
 va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const void *V,

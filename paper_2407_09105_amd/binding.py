@@ -17,7 +17,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libvarlen_attn.so")
 
 VA_OK = 0
-VA_F32, VA_BF16 = 0, 1
+VA_F32, VA_BF16, VA_F16 = 0, 1, 2
 VA_I32, VA_I64 = 0, 1
 VA_TILE = 256
 STAGE_D, STAGE_DKDV, STAGE_DQ = 1, 2, 4
@@ -95,6 +95,8 @@ def _dt(t: torch.Tensor) -> int:
         return VA_F32
     if t.dtype == torch.bfloat16:
         return VA_BF16
+    if t.dtype == torch.float16:
+        return VA_F16
     raise TypeError(f"unsupported dtype {t.dtype}")
 
 

@@ -38,7 +38,7 @@ bool use_mfma(va_dtype dt, int d) {
     const char *e = std::getenv("VA_FORCE_GENERIC");
     return e && e[0] == '1';
   }();
-  return dt == VA_BF16 && d == 128 && !force_generic;
+  return (dt == VA_BF16 || dt == VA_F16) && d <= 128 && d % 8 == 0 && !force_generic;
 }
 
 va_status check_common(const va_segments *seg, int32_t rows, int32_t T, int32_t hq, int32_t hkv,
@@ -50,11 +50,11 @@ va_status check_common(const va_segments *seg, int32_t rows, int32_t T, int32_t 
   if (rows <= 0 || T <= 0 || hq <= 0 || hkv <= 0 || d <= 0) return VA_ERR_SHAPE;
   if ((long long)rows * T >= (1ll << 31) - 1) return VA_ERR_SHAPE;
   if (hq % hkv != 0) return VA_ERR_SHAPE;
-  if (dt != VA_F32 && dt != VA_BF16) return VA_ERR_UNSUPPORTED;
+  if (dt != VA_F32 && dt != VA_BF16 && dt != VA_F16) return VA_ERR_UNSUPPORTED;
   if (d > 256) return VA_ERR_UNSUPPORTED;
   if (hq > 65535) return VA_ERR_UNSUPPORTED;  // a grid dimension of the D kernel
   // the MFMA kernels address one packed row's K/V (or Q/dO) through 32-bit byte offsets
-  if (dt == VA_BF16 && d == 128 && ((long long)T + 256) * hq * 256 >= (1ll << 32)) return VA_ERR_UNSUPPORTED;
+  if (use_mfma(dt, d) && ((long long)T + 256) * hq * d * 2 >= (1ll << 32)) return VA_ERR_UNSUPPORTED;
   return VA_OK;
 }
 
@@ -154,7 +154,7 @@ va_status va_varlen_attn_fwd(const void *Q, const void *K, const void *V, void *
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
   hipError_t e;
   if (use_mfma(dt, d))
-    e = va::launch_mfma_fwd(Q, K, V, O, LSE, *seg, rows, tokens_per_row, hq, hkv, scale, (hipStream_t)stream);
+    e = va::launch_mfma_fwd(Q, K, V, O, LSE, *seg, rows, tokens_per_row, hq, hkv, d, dt, scale, (hipStream_t)stream);
   else
     e = va::launch_generic_fwd(Q, K, V, O, LSE, *seg, N, hq, hkv, d, dt, scale, (hipStream_t)stream);
   return e == hipSuccess ? VA_OK : VA_ERR_HIP;
@@ -169,7 +169,9 @@ va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K
   if (!dO || !Q || !K || !V || !O || !LSE || !dQ || !dK || !dV) return VA_ERR_NULL;
   va_status s = check_common(seg, rows, tokens_per_row, hq, hkv, d, dt);
   if (s != VA_OK) return s;
-  if (grad_dt != VA_F32 && grad_dt != VA_BF16) return VA_ERR_UNSUPPORTED;
+  // gradients come out in fp32 or in the inputs' own 16-bit type (fp32 inputs: fp32 or bf16)
+  if (grad_dt != VA_F32 && !(grad_dt == VA_BF16 && dt != VA_F16) && !(grad_dt == VA_F16 && dt == VA_F16))
+    return VA_ERR_UNSUPPORTED;
   if (stages == 0 || (stages & ~(VA_STAGE_D | VA_STAGE_DKDV | VA_STAGE_DQ))) return VA_ERR_UNSUPPORTED;
   const int N = rows * tokens_per_row;
   const size_t need = va_attn_workspace_bytes(N, hq, hkv, d, 1);
@@ -184,7 +186,7 @@ va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K
   if (stages & (VA_STAGE_DKDV | VA_STAGE_DQ)) {
     if (use_mfma(dt, d))
       e = va::launch_mfma_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, rows, tokens_per_row, hq,
-                              hkv, scale, st, stages);
+                              hkv, d, dt, scale, st, stages);
     else
       e = va::launch_generic_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, N, hq, hkv, d, dt, scale,
                                  st, stages);

@@ -1,4 +1,4 @@
-// Backward kernels: dQ (query-major) and dK/dV (key-major), bf16, head_dim 128.
+// Backward kernels: dQ (query-major) and dK/dV (key-major), bf16 / fp16, head_dim <= 128.
 //
 // What they compute (see include/varlen_attn.h), from the saved LSE and D = rowsum(dO * O):
 //   P_ij = exp(scale q_i.k_j - LSE_i),  dP_ij = dO_i.v_j,  dS_ij = P_ij (dP_ij - D_i)
@@ -28,13 +28,18 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 
 // ---------------------------------------------------------------------------------------------
-template <bool kF32Out>
+// Template parameters of both kernels: E element type of the inputs (Bf16 / F16); EOut the
+// gradients' type (float, or E); kDh head_dim rounded up to 64, 96 or 128 (the unrolling); the
+// argument d is the tensors' head_dim (a multiple of 8, <= kDh).
+template <class E, class EOut, int kDh>
 __global__ void __launch_bounds__(256, 2)
 dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
                const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
                const float *__restrict__ LSE, const float *__restrict__ delta, void *__restrict__ dQ,
                const int32_t *__restrict__ seg_start, const int32_t *__restrict__ q_tile_order, int N,
-               int T, int tiles_per_row, int hq, int hkv, float scale_log2, float scale) {
+               int T, int tiles_per_row, int hq, int hkv, int d, float scale_log2, float scale) {
+  constexpr int kKs = kDh / 16, kCb = kDh / 32;
+  typedef typename E::x8 x8;
   // two stages of {K block, V block}, swizzled
   __shared__ __attribute__((aligned(16))) uint16_t lds[4 * kBlk];
   static_assert(4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit");
@@ -65,21 +70,15 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   const int i_ld = min(i_abs, t_last);  // clamped: loads stay in bounds, results of dead rows are dropped
   const int ss_i = row_ok ? seg_start[i_ld] : 0x7fffffff;
 
-  bf16x8 qf[8], gf[8];  // Q and dO rows of this lane: B operands
-  {
-    const size_t off = ((size_t)i_ld * hq + h) * kD + half * 8;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      qf[ks] = as_bf16x8(*(const u32x4 *)(Q + off + ks * 16));
-      gf[ks] = as_bf16x8(*(const u32x4 *)(dO + off + ks * 16));
-    }
-  }
+  x8 qf[kKs], gf[kKs];  // Q and dO rows of this lane: B operands
+  load_row_fragments<E, kKs>(Q + ((size_t)i_ld * hq + h) * d, d, half, qf);
+  load_row_fragments<E, kKs>(dO + ((size_t)i_ld * hq + h) * d, d, half, gf);
   const float lse2 = LSE[(size_t)h * N + i_ld] * kLog2e;
   const float dl = delta[(size_t)h * N + i_ld];
 
-  f32x16 acc[4];
+  f32x16 acc[kCb];
 #pragma unroll
-  for (int cb = 0; cb < 4; ++cb)
+  for (int cb = 0; cb < kCb; ++cb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[cb][v] = 0.f;
 
@@ -87,7 +86,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   uint32_t tr_lane[2];
   swz_tr_lane_off(lane, tr_lane);
 
-  const size_t row_bytes = (size_t)hkv * kD * 2;
+  const size_t row_bytes = (size_t)hkv * d * 2;
   const size_t base_off = (size_t)jb_lo * kBS * row_bytes;
   const size_t total = (size_t)N * row_bytes;
   const buffer_t kbuf = make_buffer((const char *)K + base_off, total - base_off);
@@ -96,7 +95,8 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   // tensor, each 1 KB = 4 rows at LDS address (4 p + wave) KB; lane L lands at row 16 p + 4 wave + L / 16,
   // chunk position L % 16, and fetches global chunk (L % 16) ^ swz(row).
   const int dma_row = wave * 4 + (lane >> 4);
-  const uint32_t dma_off = (uint32_t)(dma_row * row_bytes + g * kD * 2 + (((lane & 15) ^ swz(dma_row)) << 4));
+  const uint32_t dma_off = dma_lane_offset(lane, dma_row, row_bytes, g, d);
+  const bool dma_ok = dma_lane_ok(lane, dma_row, d);  // the same for all four transfers (rows 16 apart)
   const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
   const uint32_t p_bytes = (uint32_t)(16 * row_bytes);
   typedef __attribute__((address_space(3))) void *lds_void;
@@ -104,8 +104,9 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
     const uint32_t off = dma_off + (uint32_t)(jb - jb_lo) * blk_bytes;
 #pragma unroll
     for (int p = 0; p < 4; ++p) {
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
+      const uint32_t o = dma_ok ? off + p * p_bytes : kPastEnd;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, o, 0, 0, 0);
     }
   };
 
@@ -124,9 +125,9 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 #pragma unroll
         for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) {
-          s = mfma32(swz_read_row(Kb, row_lane, ks, sb * 32), qf[ks], s);     // S^T  = K Q^T
-          dp = mfma32(swz_read_row(Vb, row_lane, ks, sb * 32), gf[ks], dp);   // dP^T = V dO^T
+        for (int ks = 0; ks < kKs; ++ks) {
+          s = mfma32(swz_read_row<E>(Kb, row_lane, ks, sb * 32), qf[ks], s);     // S^T  = K Q^T
+          dp = mfma32(swz_read_row<E>(Vb, row_lane, ks, sb * 32), gf[ks], dp);   // dP^T = V dO^T
         }
         const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
 #pragma unroll
@@ -140,10 +141,10 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
         }
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8 df = pack_bf16x8(s, 8 * s2);
+          const x8 df = pack_x8<E>(s, 8 * s2);
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb)  // dQ^T += K^T dS^T
-            acc[cb] = mfma32(swz_read_tr(Kb, tr_lane, cb, sb * 32 + s2 * 16), df, acc[cb]);
+          for (int cb = 0; cb < kCb; ++cb)  // dQ^T += K^T dS^T
+            acc[cb] = mfma32(swz_read_tr<E>(Kb, tr_lane, cb, sb * 32 + s2 * 16), df, acc[cb]);
         }
       }
     }
@@ -160,7 +161,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   }
 
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
-  store_transposed_tile<kF32Out>(acc, scale, stage, dQ, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h);
+  store_transposed_tile<EOut, kCb>(acc, scale, stage, dQ, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h, d);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -178,14 +179,16 @@ __device__ __forceinline__ void lds_barrier() {  // LDS traffic of this wave don
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-template <bool kF32Out>
+template <class E, class EOut, int kDh>
 __global__ void __launch_bounds__(kDkdvThreads, 1)
 dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
                   const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
                   const float *__restrict__ LSE, const float *__restrict__ delta, void *__restrict__ dK,
                   void *__restrict__ dV, const int32_t *__restrict__ seg_end,
                   const int32_t *__restrict__ kv_tile_order, int N, int T, int tiles_per_row, int hq,
-                  int hkv, float scale_log2, float scale) {
+                  int hkv, int d, float scale_log2, float scale) {
+  constexpr int kKs = kDh / 16, kCb = kDh / 32;
+  typedef typename E::x8 x8;
   // two stages of {Q block, dO block (swizzled), -LSE / scale [64], -D [64]}; reused as the staging
   // area of the result stores (8 waves)
   constexpr int kStage = 2 * kBlk + 4 * kBS;
@@ -209,14 +212,15 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const int t_last = min(t0 + kBT, row_end) - 1;
   const int ib_lo = t0 / kBS;
 
-  const size_t row_bytes = (size_t)hq * kD * 2;
+  const size_t row_bytes = (size_t)hq * d * 2;
   const size_t base_off = (size_t)ib_lo * kBS * row_bytes;
   const size_t total = (size_t)N * row_bytes;
   const buffer_t qbuf = make_buffer((const char *)Q + base_off, total - base_off);
   const buffer_t gbuf = make_buffer((const char *)dO + base_off, total - base_off);
   // HBM -> LDS copy of a 64-row block: 16 transfers of 1 KB (4 rows) per tensor, two per wave
   const int dma_row = wave * 4 + (lane >> 4);  // and 32 rows further for the second transfer (same swizzle)
-  const uint32_t dma_off = (uint32_t)(dma_row * row_bytes + (((lane & 15) ^ swz(dma_row)) << 4));
+  const uint32_t dma_off = dma_lane_offset(lane, dma_row, row_bytes, 0, d);
+  const bool dma_ok = dma_lane_ok(lane, dma_row, d);
   const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
   const uint32_t p_bytes = (uint32_t)(32 * row_bytes);
   typedef __attribute__((address_space(3))) void *lds_void;
@@ -230,12 +234,12 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
       const int i = min(ib * kBS + stat_row, N - 1);
       rstat = stat_src[(size_t)(g * G + hh) * N + i];
     }
-    const uint32_t off = dma_off + (uint32_t)(ib - ib_lo) * blk_bytes + (uint32_t)((g * G + hh) * kD * 2);
+    const uint32_t off = dma_off + (uint32_t)(ib - ib_lo) * blk_bytes + (uint32_t)((g * G + hh) * d * 2);
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(qbuf, (lds_void)(dst + (8 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(gbuf, (lds_void)(dst + kBlk + (8 * p + wave) * 512), 16,
-                                               off + p * p_bytes, 0, 0, 0);
+      const uint32_t o = dma_ok ? off + p * p_bytes : kPastEnd;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(qbuf, (lds_void)(dst + (8 * p + wave) * 512), 16, o, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(gbuf, (lds_void)(dst + kBlk + (8 * p + wave) * 512), 16, o, 0, 0, 0);
     }
   };
   auto put_stats = [&](uint16_t *dst) {
@@ -259,16 +263,11 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const int j_ld = min(j_abs, t_last);
   const int se_j = row_ok ? seg_end[j_ld] : 0;
 
-  bf16x8 rf[8];  // this lane's key row: K (V side computes S) or V (K side computes dP)
-  {
-    const uint16_t *src = k_side ? V : K;
-    const size_t off = ((size_t)j_ld * hkv + g) * kD + half * 8;
+  x8 rf[kKs];  // this lane's key row: K (V side computes S) or V (K side computes dP)
+  load_row_fragments<E, kKs>((k_side ? V : K) + ((size_t)j_ld * hkv + g) * d, d, half, rf);
+  f32x16 acc[kCb];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) rf[ks] = as_bf16x8(*(const u32x4 *)(src + off + ks * 16));
-  }
-  f32x16 acc[4];
-#pragma unroll
-  for (int cb = 0; cb < 4; ++cb)
+  for (int cb = 0; cb < kCb; ++cb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[cb][v] = 0.f;
 
@@ -292,7 +291,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
       const int il = i0 + sb * 32, row0 = sb * 32;
       const bool active = wave_ok && il + 31 >= jw0 && il < se_max;  // wave-uniform, same for both sides
       f32x16 x;
-      bf16x8 ty[2][4];
+      x8 ty[2][kCb];
       if (active) {
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
@@ -300,15 +299,15 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 #pragma unroll
           for (int b = 0; b < 4; ++b) x[q4 * 4 + b] = c[b];
         }
-        bf16x8 ax[8];
+        x8 ax[kKs];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) ax[ks] = swz_read_row(Xs, row_lane, ks, row0);
+        for (int ks = 0; ks < kKs; ++ks) ax[ks] = swz_read_row<E>(Xs, row_lane, ks, row0);
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) x = mfma32(ax[ks], rf[ks], x);  // S - LSE / scale, or dP - D
+        for (int ks = 0; ks < kKs; ++ks) x = mfma32(ax[ks], rf[ks], x);  // S - LSE / scale, or dP - D
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb) ty[s2][cb] = swz_read_tr(Ys, tr_lane, cb, row0 + s2 * 16);
+          for (int cb = 0; cb < kCb; ++cb) ty[s2][cb] = swz_read_tr<E>(Ys, tr_lane, cb, row0 + s2 * 16);
         if (!k_side) {
 #pragma unroll
           for (int v = 0; v < 16; ++v) x[v] = __builtin_amdgcn_exp2f(x[v] * scale_log2);  // P
@@ -320,24 +319,24 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
               if (i < j_abs || i >= se_j) x[v] = 0.f;
             }
           }
-          ex[par * 128] = __builtin_bit_cast(u32x4, pack_bf16x8(x, 0));
-          ex[par * 128 + 64] = __builtin_bit_cast(u32x4, pack_bf16x8(x, 8));
+          ex[par * 128] = __builtin_bit_cast(u32x4, pack_x8<E>(x, 0));
+          ex[par * 128 + 64] = __builtin_bit_cast(u32x4, pack_x8<E>(x, 8));
         }
       }
       lds_barrier();  // P of this sub-block is in LDS
       if (active) {
-        bf16x8 f0, f1;
+        x8 f0, f1;
         if (k_side) {
-          const bf16x8 p0 = as_bf16x8(ex[par * 128]), p1 = as_bf16x8(ex[par * 128 + 64]);
+          const x8 p0 = as_x8<E>(ex[par * 128]), p1 = as_x8<E>(ex[par * 128 + 64]);
 #pragma unroll
           for (int e = 0; e < 8; ++e) { x[e] *= (float)p0[e]; x[8 + e] *= (float)p1[e]; }  // dS
         }
-        f0 = pack_bf16x8(x, 0);
-        f1 = pack_bf16x8(x, 8);
+        f0 = pack_x8<E>(x, 0);
+        f1 = pack_x8<E>(x, 8);
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb) acc[cb] = mfma32(ty[0][cb], f0, acc[cb]);  // dV^T += dO^T P, dK^T += Q^T dS
+        for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(ty[0][cb], f0, acc[cb]);  // dV^T += dO^T P, dK^T += Q^T dS
 #pragma unroll
-        for (int cb = 0; cb < 4; ++cb) acc[cb] = mfma32(ty[1][cb], f1, acc[cb]);
+        for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(ty[1][cb], f1, acc[cb]);
       }
       par ^= 1;
     }
@@ -357,40 +356,61 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   float *stage = (float *)stages + wave * kStageFloatsPerWave;
   const int nrows = wave_ok ? jw1 - jw0 + 1 : 0;
   if (k_side)
-    store_transposed_tile<kF32Out>(acc, scale, stage, dK, jw0, nrows, hkv, g);
+    store_transposed_tile<EOut, kCb>(acc, scale, stage, dK, jw0, nrows, hkv, g, d);
   else
-    store_transposed_tile<kF32Out>(acc, 1.f, stage, dV, jw0, nrows, hkv, g);
+    store_transposed_tile<EOut, kCb>(acc, 1.f, stage, dV, jw0, nrows, hkv, g, d);
 }
 
 }  // namespace
 
+template <class E, class EOut, int kDh>
+static void launch_bwd_t(const uint16_t *g, const uint16_t *q, const uint16_t *k, const uint16_t *v,
+                         const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
+                         const va_segments &seg, int N, int T, int tiles_per_row, int hq, int hkv, int d,
+                         float scale, unsigned gq, unsigned gkv, hipStream_t stream, unsigned stages) {
+  const float scale_log2 = scale * kLog2e;
+  if (stages & VA_STAGE_DKDV)
+    dkdv_mfma_kernel<E, EOut, kDh><<<gkv, kDkdvThreads, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
+                                                                     seg.kv_tile_order, N, T, tiles_per_row, hq,
+                                                                     hkv, d, scale_log2, scale);
+  if (stages & VA_STAGE_DQ)
+    dq_mfma_kernel<E, EOut, kDh><<<gq, 256, 0, stream>>>(g, q, k, v, LSE, delta, dQ, seg.seg_start,
+                                                         seg.q_tile_order, N, T, tiles_per_row, hq, hkv, d,
+                                                         scale_log2, scale);
+}
+
+template <class E, class EOut, class... A>
+static void launch_bwd_d(int d, A... a) {
+  if (d <= 64) launch_bwd_t<E, EOut, 64>(a...);
+  else if (d <= 96) launch_bwd_t<E, EOut, 96>(a...);
+  else launch_bwd_t<E, EOut, 128>(a...);
+}
+
 hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const void *V,
                            const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
                            va_dtype grad_dt, const va_segments &seg, int rows, int T, int hq,
-                           int hkv, float scale, hipStream_t stream, unsigned stages) {
+                           int hkv, int d, va_dtype dt, float scale, hipStream_t stream, unsigned stages) {
   const int tiles_per_row = ceil_div(T, VA_TILE);
   const long long ntiles = (long long)rows * tiles_per_row * kSub;
   if (ntiles * hq > 0x7fffffffll) return hipErrorInvalidValue;
   const int N = rows * T;
-  const float scale_log2 = scale * kLog2e;
   const uint16_t *q = (const uint16_t *)Q, *k = (const uint16_t *)K, *v = (const uint16_t *)V,
                  *g = (const uint16_t *)dO;
   const unsigned gq = (unsigned)(ntiles * hq), gkv = (unsigned)(ntiles * hkv);
-  const bool do_kv = stages & VA_STAGE_DKDV, do_q = stages & VA_STAGE_DQ;
-  if (grad_dt == VA_F32) {
-    if (do_kv) dkdv_mfma_kernel<true><<<gkv, kDkdvThreads, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
-                                                              seg.kv_tile_order, N, T, tiles_per_row, hq, hkv,
-                                                              scale_log2, scale);
-    if (do_q) dq_mfma_kernel<true><<<gq, 256, 0, stream>>>(g, q, k, v, LSE, delta, dQ, seg.seg_start,
-                                                 seg.q_tile_order, N, T, tiles_per_row, hq, hkv,
-                                                 scale_log2, scale);
+  if (dt == VA_F16) {
+    if (grad_dt == VA_F32)
+      launch_bwd_d<F16, float>(d, g, q, k, v, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
+                               gq, gkv, stream, stages);
+    else
+      launch_bwd_d<F16, F16>(d, g, q, k, v, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
+                             gq, gkv, stream, stages);
   } else {
-    if (do_kv) dkdv_mfma_kernel<false><<<gkv, kDkdvThreads, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
-                                                               seg.kv_tile_order, N, T, tiles_per_row, hq, hkv,
-                                                               scale_log2, scale);
-    if (do_q) dq_mfma_kernel<false><<<gq, 256, 0, stream>>>(g, q, k, v, LSE, delta, dQ, seg.seg_start,
-                                                  seg.q_tile_order, N, T, tiles_per_row, hq, hkv,
-                                                  scale_log2, scale);
+    if (grad_dt == VA_F32)
+      launch_bwd_d<Bf16, float>(d, g, q, k, v, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
+                                gq, gkv, stream, stages);
+    else
+      launch_bwd_d<Bf16, Bf16>(d, g, q, k, v, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
+                               gq, gkv, stream, stages);
   }
   return hipGetLastError();
 }

@@ -1,4 +1,4 @@
-// Forward kernel: causal attention inside each example of a packed stream, bf16, head_dim 128.
+// Forward kernel: causal attention inside each example of a packed stream, bf16 / fp16, head_dim <= 128.
 //
 // What it computes (see include/varlen_attn.h): O_i = softmax_j(scale q_i.k_j) v_j over the keys
 // a <= j <= i of token i's own example, and LSE_i.  The example bound a = seg_start[i] comes from
@@ -33,11 +33,16 @@ constexpr int kBlk = kBN * kD;    // elements of one swizzled [32][128] LDS bloc
 constexpr int kLdsElems = (4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4) ? 4 * kBlk : 4 * kStageFloatsPerWave * 2;
 constexpr float kLazyLog2 = 8.f;  // keep a stale row maximum while probabilities stay <= 2^8
 
+// E: element type (Bf16 / F16); kDh: head_dim rounded up to 64, 96 or 128 (k-steps and column blocks
+// the kernel is unrolled for); d: the tensors' head_dim (a multiple of 8, <= kDh).
+template <class E, int kDh>
 __global__ void __launch_bounds__(256, 3)
 fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
                 const uint16_t *__restrict__ V, uint16_t *__restrict__ O, float *__restrict__ LSE,
                 const int32_t *__restrict__ seg_start, const int32_t *__restrict__ q_tile_order,
-                int N, int T, int tiles_per_row, int hq, int hkv, float scale_log2, float scale) {
+                int N, int T, int tiles_per_row, int hq, int hkv, int d, float scale_log2, float scale) {
+  constexpr int kKs = kDh / 16, kCb = kDh / 32;
+  typedef typename E::x8 x8;
   // stage 0 = {K, V} at lds[0 .. 2 kBlk), stage 1 = {K, V} at lds[2 kBlk .. 4 kBlk)
   __shared__ __attribute__((aligned(16))) uint16_t lds[kLdsElems];
 
@@ -72,18 +77,18 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   const int i_ld = min(i_abs, t_last);  // clamped: loads stay in bounds, results of dead rows are dropped
   const int ss_i = row_ok ? seg_start[i_ld] : 0x7fffffff;
 
-  bf16x8 qf[8];  // B operands of S^T = K Q^T; 8 k-steps of 16 (loaded below, behind the first block copy)
+  x8 qf[kKs];  // B operands of S^T = K Q^T; k-steps of 16 (loaded below, behind the first block copy)
 
-  f32x16 o_acc[4];
+  f32x16 o_acc[kCb];
 #pragma unroll
-  for (int cb = 0; cb < 4; ++cb)
+  for (int cb = 0; cb < kCb; ++cb)
 #pragma unroll
     for (int v = 0; v < 16; ++v) o_acc[cb][v] = 0.f;
   float m_ref = -INFINITY;  // reference maximum the stored probabilities are relative to (raw scores)
   float l_run = 0.f;        // this lane's share of the running row sum, relative to m_ref
 
   // K/V block loads: buffer descriptors based at the workgroup's first key row
-  const size_t row_bytes = (size_t)hkv * kD * 2;
+  const size_t row_bytes = (size_t)hkv * d * 2;
   const size_t base_off = (size_t)jb_lo * kBN * row_bytes;
   const size_t total = (size_t)N * row_bytes;
   const buffer_t kbuf = make_buffer((const char *)K + base_off, total - base_off);
@@ -92,7 +97,8 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   // 1 KB (4 rows) at wave-uniform LDS address (4 p + wave) KB; lane L lands at row 16 p + 4 wave + L / 16,
   // chunk position L % 16, and therefore fetches global chunk (L % 16) ^ swz(row) of that row.
   const int dma_row = wave * 4 + (lane >> 4);
-  const uint32_t dma_off = (uint32_t)(dma_row * row_bytes + g * kD * 2 + (((lane & 15) ^ swz(dma_row)) << 4));
+  const uint32_t dma_off = dma_lane_offset(lane, dma_row, row_bytes, g, d);
+  const bool dma_ok = dma_lane_ok(lane, dma_row, d);  // same for every transfer of this lane (rows 16 apart)
   const uint32_t blk_bytes = (uint32_t)(kBN * row_bytes);
   const uint32_t p_bytes = (uint32_t)(16 * row_bytes);
   typedef __attribute__((address_space(3))) void *lds_void;
@@ -100,8 +106,9 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     const uint32_t off = dma_off + (uint32_t)(jb - jb_lo) * blk_bytes;
 #pragma unroll
     for (int p = 0; p < kBN / 16; ++p) {
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, off + p * p_bytes, 0, 0, 0);
+      const uint32_t o = dma_ok ? off + p * p_bytes : kPastEnd;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, o, 0, 0, 0);
     }
   };
 
@@ -121,7 +128,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) s = mfma32(swz_read_row(Kb, row_lane, ks, sb * 32), qf[ks], s);
+        for (int ks = 0; ks < kKs; ++ks) s = mfma32(swz_read_row<E>(Kb, row_lane, ks, sb * 32), qf[ks], s);
         const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
         if (!interior) {
 #pragma unroll
@@ -140,7 +147,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
           const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * scale_log2);
           l_run *= alpha;
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb)
+          for (int cb = 0; cb < kCb; ++cb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) o_acc[cb][v] *= alpha;
           m_ref = m_new;
@@ -158,10 +165,10 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
         // ---- O^T += V^T P^T ----
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
-          const bf16x8 pf = pack_bf16x8(s, 8 * s2);
+          const x8 pf = pack_x8<E>(s, 8 * s2);
 #pragma unroll
-          for (int cb = 0; cb < 4; ++cb)
-            o_acc[cb] = mfma32(swz_read_tr(Vb, tr_lane, cb, sb * 32 + s2 * 16), pf, o_acc[cb]);
+          for (int cb = 0; cb < kCb; ++cb)
+            o_acc[cb] = mfma32(swz_read_tr<E>(Vb, tr_lane, cb, sb * 32 + s2 * 16), pf, o_acc[cb]);
         }
       }
     }
@@ -170,11 +177,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
 
   uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
   copy_block(K0, V0, jb_lo);  // in flight while the Q fragments are fetched
-  {
-    const uint16_t *qp = Q + ((size_t)i_ld * hq + h) * kD + half * 8;
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qf[ks] = as_bf16x8(*(const u32x4 *)(qp + ks * 16));
-  }
+  load_row_fragments<E, kKs>(Q + ((size_t)i_ld * hq + h) * d, d, half, qf);
   wait_all_loads();  // Q fragments too: inside the loop only block copies are in flight
   __syncthreads();
   for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
@@ -187,22 +190,37 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   const float inv = row_ok ? 1.f / l_tot : 0.f;
   if (row_ok && half == 0) LSE[(size_t)h * N + i_abs] = m_ref * scale + __logf(l_tot);
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
-  store_transposed_tile<false>(o_acc, inv, stage, O, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h);
+  store_transposed_tile<E, kCb>(o_acc, inv, stage, O, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h, d);
 }
 
 }  // namespace
 
+template <class E>
+static void launch_fwd_e(const void *Q, const void *K, const void *V, void *O, float *LSE, const va_segments &seg,
+                         int rows, int T, int hq, int hkv, int d, float scale, unsigned nwg, hipStream_t stream) {
+  const int tiles_per_row = ceil_div(T, VA_TILE);
+  const float scale_log2 = scale * 1.4426950408889634f;
+  const uint16_t *q = (const uint16_t *)Q, *k = (const uint16_t *)K, *v = (const uint16_t *)V;
+#define VA_LAUNCH_FWD(DH)                                                                             \
+  fwd_mfma_kernel<E, DH><<<nwg, 256, 0, stream>>>(q, k, v, (uint16_t *)O, LSE, seg.seg_start,          \
+                                                  seg.q_tile_order, rows * T, T, tiles_per_row, hq,   \
+                                                  hkv, d, scale_log2, scale)
+  if (d <= 64) VA_LAUNCH_FWD(64);
+  else if (d <= 96) VA_LAUNCH_FWD(96);
+  else VA_LAUNCH_FWD(128);
+#undef VA_LAUNCH_FWD
+}
+
 hipError_t launch_mfma_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
-                           const va_segments &seg, int rows, int T, int hq, int hkv, float scale,
-                           hipStream_t stream) {
+                           const va_segments &seg, int rows, int T, int hq, int hkv, int d, va_dtype dt,
+                           float scale, hipStream_t stream) {
   const int tiles_per_row = ceil_div(T, VA_TILE);
   const long long nwg = (long long)rows * tiles_per_row * kSub * hq;
   if (nwg <= 0 || nwg > 0x7fffffffll) return hipErrorInvalidValue;
-  const float scale_log2 = scale * 1.4426950408889634f;
-  fwd_mfma_kernel<<<(unsigned)nwg, 256, 0, stream>>>((const uint16_t *)Q, (const uint16_t *)K,
-                                                     (const uint16_t *)V, (uint16_t *)O, LSE,
-                                                     seg.seg_start, seg.q_tile_order, rows * T, T,
-                                                     tiles_per_row, hq, hkv, scale_log2, scale);
+  if (dt == VA_F16)
+    launch_fwd_e<F16>(Q, K, V, O, LSE, seg, rows, T, hq, hkv, d, scale, (unsigned)nwg, stream);
+  else
+    launch_fwd_e<Bf16>(Q, K, V, O, LSE, seg, rows, T, hq, hkv, d, scale, (unsigned)nwg, stream);
   return hipGetLastError();
 }
 

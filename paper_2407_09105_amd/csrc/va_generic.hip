@@ -1,10 +1,11 @@
-// Plain fp32-arithmetic kernels: any element type (fp32 / bf16), any head_dim <= 256.
+// Plain fp32-arithmetic kernels: any element type (fp32 / bf16 / fp16), any head_dim <= 256.
 //
 // They serve the fp32 path (where bf16 matrix cores cannot give the required accuracy) and
 // head dims the MFMA kernels are not instantiated for.  One 64-lane wave per output row; the
 // lanes split the head dimension; the mask is "seg_start[i] <= j <= i" (forward, dQ) or
 // "j <= i < seg_end[j]" (dK/dV) -- Table 1's correct cross-attention for contiguous examples.
 #include "va_internal.h"
+#include "va_mfma_common.h"
 
 namespace va {
 namespace {
@@ -22,6 +23,9 @@ __device__ __forceinline__ void st(uint16_t *p, size_t i, float x) {
   u += 0x7fffu + ((u >> 16) & 1u);  // round to nearest even
   p[i] = (uint16_t)(u >> 16);
 }
+
+__device__ __forceinline__ float ld(const _Float16 *p, size_t i) { return (float)p[i]; }
+__device__ __forceinline__ void st(_Float16 *p, size_t i, float x) { p[i] = (_Float16)x; }
 
 __device__ __forceinline__ float wave_sum(float x) {
   for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, 64);
@@ -92,25 +96,23 @@ delta_kernel(const T *__restrict__ dO, const T *__restrict__ O, float *__restric
   if (lane == 0) delta[(size_t)h * N + i] = part;
 }
 
-// D for bf16, head_dim 128: 16 lanes per (token, head) row, 16 B of dO and of O per lane; a block
-// handles 64 consecutive tokens of one head, so the [Hq, N] result is written 64 B at a time.
+// D for the 16-bit types with head_dim a multiple of 8 up to 128: 16 lanes per (token, head) row,
+// 16 B of dO and of O per lane; a block handles 64 consecutive tokens of one head, so the [Hq, N]
+// result is written 64 B at a time.
+template <class E>
 __global__ void __launch_bounds__(256)
-delta_bf16_d128_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ O,
-                       float *__restrict__ delta, int N, int hq) {
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+delta_16bit_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ O,
+                   float *__restrict__ delta, int N, int hq, int d) {
   const int h = blockIdx.y, c = threadIdx.x & 15, ti = threadIdx.x >> 4;
 #pragma unroll
   for (int it = 0; it < 4; ++it) {
     const int i = blockIdx.x * 64 + it * 16 + ti;
     float part = 0.f;
-    if (i < N) {
-      const size_t x = ((size_t)i * hq + h) * 128 + c * 8;
-      const u32x4 a = *(const u32x4 *)(dO + x), b = *(const u32x4 *)(O + x);
+    if (i < N && c * 8 < d) {
+      const size_t x = ((size_t)i * hq + h) * d + c * 8;
+      const typename E::x8 a = as_x8<E>(*(const u32x4 *)(dO + x)), b = as_x8<E>(*(const u32x4 *)(O + x));
 #pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        part += __uint_as_float(a[e] << 16) * __uint_as_float(b[e] << 16);
-        part += __uint_as_float(a[e] & 0xffff0000u) * __uint_as_float(b[e] & 0xffff0000u);
-      }
+      for (int e = 0; e < 8; ++e) part += (float)a[e] * (float)b[e];
     }
     for (int o = 8; o > 0; o >>= 1) part += __shfl_xor(part, o, 64);
     if (c == 0 && i < N) delta[(size_t)h * N + i] = part;
@@ -226,6 +228,10 @@ hipError_t launch_generic_fwd(const void *Q, const void *K, const void *V, void 
   if (dt == VA_F32)
     generic_fwd_kernel<float><<<nb, 256, 0, stream>>>((const float *)Q, (const float *)K, (const float *)V,
                                                       (float *)O, LSE, seg.seg_start, N, hq, hkv, d, scale);
+  else if (dt == VA_F16)
+    generic_fwd_kernel<_Float16><<<nb, 256, 0, stream>>>((const _Float16 *)Q, (const _Float16 *)K,
+                                                         (const _Float16 *)V, (_Float16 *)O, LSE,
+                                                         seg.seg_start, N, hq, hkv, d, scale);
   else
     generic_fwd_kernel<uint16_t><<<nb, 256, 0, stream>>>((const uint16_t *)Q, (const uint16_t *)K,
                                                          (const uint16_t *)V, (uint16_t *)O, LSE,
@@ -235,13 +241,18 @@ hipError_t launch_generic_fwd(const void *Q, const void *K, const void *V, void 
 
 hipError_t launch_delta(const void *dO, const void *O, float *delta, int N, int hq, int d,
                         va_dtype dt, hipStream_t stream) {
-  if (dt == VA_BF16 && d == 128) {
-    delta_bf16_d128_kernel<<<dim3((unsigned)((N + 63) / 64), (unsigned)hq), 256, 0, stream>>>(
-        (const uint16_t *)dO, (const uint16_t *)O, delta, N, hq);
+  if (dt != VA_F32 && d <= 128 && d % 8 == 0) {
+    const dim3 grid((unsigned)((N + 63) / 64), (unsigned)hq);
+    if (dt == VA_F16)
+      delta_16bit_kernel<F16><<<grid, 256, 0, stream>>>((const uint16_t *)dO, (const uint16_t *)O, delta, N, hq, d);
+    else
+      delta_16bit_kernel<Bf16><<<grid, 256, 0, stream>>>((const uint16_t *)dO, (const uint16_t *)O, delta, N, hq, d);
     return hipGetLastError();
   }
   const unsigned nb = blocks_for((long long)N * hq);
-  if (dt == VA_F32)
+  if (dt == VA_F16)
+    delta_kernel<_Float16><<<nb, 256, 0, stream>>>((const _Float16 *)dO, (const _Float16 *)O, delta, N, hq, d);
+  else if (dt == VA_F32)
     delta_kernel<float><<<nb, 256, 0, stream>>>((const float *)dO, (const float *)O, delta, N, hq, d);
   else
     delta_kernel<uint16_t><<<nb, 256, 0, stream>>>((const uint16_t *)dO, (const uint16_t *)O, delta, N, hq, d);
@@ -266,7 +277,11 @@ hipError_t launch_generic_bwd(const void *dO, const void *Q, const void *K, cons
                               const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
                               va_dtype grad_dt, const va_segments &seg, int N, int hq, int hkv,
                               int d, va_dtype dt, float scale, hipStream_t stream, unsigned stages) {
-  if (dt == VA_F32 && grad_dt == VA_F32)
+  if (dt == VA_F16 && grad_dt == VA_F32)
+    launch_bwd_t<_Float16, float>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream, stages);
+  else if (dt == VA_F16)
+    launch_bwd_t<_Float16, _Float16>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream, stages);
+  else if (dt == VA_F32 && grad_dt == VA_F32)
     launch_bwd_t<float, float>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream, stages);
   else if (dt == VA_F32)
     launch_bwd_t<float, uint16_t>(dO, Q, K, V, LSE, delta, dQ, dK, dV, seg, N, hq, hkv, d, scale, stream, stages);

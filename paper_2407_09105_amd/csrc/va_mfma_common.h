@@ -1,6 +1,6 @@
-// Shared device helpers of the bf16 MFMA kernels (head_dim 128, gfx950).
+// Shared device helpers of the MFMA kernels (bf16 / fp16, head_dim <= 128, gfx950).
 //
-// Matrix-core tile used throughout: v_mfma_f32_32x32x16_bf16, D[32x32] += A[32x16] * B[16x32].
+// Matrix-core tile used throughout: v_mfma_f32_32x32x16_{bf16,f16}, D[32x32] += A[32x16] * B[16x32].
 // Register layout per 64-lane wave (lane l, half = l / 32):
 //   A : lane holds row  l % 32, k = 8 * half .. 8 * half + 7   (8 bf16, contiguous in k)
 //   B : lane holds col  l % 32, k = 8 * half .. 8 * half + 7
@@ -22,39 +22,55 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kD = 128;  // head_dim of the MFMA kernels
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// LDS rows of a streamed block always hold 128 elements (256 B); a kernel instantiated for a
+// padded head_dim kDh (64, 96 or 128) uses the first kDh of them, and a tensor whose head_dim d is
+// smaller than kDh contributes zeros for the columns d..kDh-1 (they add nothing to any product).
+constexpr int kD = 128;
 
 __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
+__device__ __forceinline__ f32x16 mfma32(f16x8 a, f16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
 
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
+// The two 16-bit element types: 8-element operand vector, conversions (round to nearest even).
+struct Bf16 {
+  typedef bf16x8 x8;
+  typedef __bf16 elem;
+};
+struct F16 {
+  typedef f16x8 x8;
+  typedef _Float16 elem;
+};
+template <class E> __device__ __forceinline__ typename E::x8 as_x8(u32x4 x) {
+  return __builtin_bit_cast(typename E::x8, x);
+}
 
 // Row (register axis) index of accumulator element v for a lane of the given half.
 __device__ __forceinline__ int acc_row(int v, int half) { return 8 * (v >> 2) + 4 * half + (v & 3); }
 
 // Eight consecutive accumulator floats v0..v0+7 -> one B operand (8 bf16).  With the layout
 // above these are rows {8a + 4 half + b : a in {2s2, 2s2+1}, b in 0..3} of a 16-row k-step.
-__device__ __forceinline__ bf16x8 pack_bf16x8(const f32x16 &x, int v0) {
-  bf16x8 r;
+template <class E> __device__ __forceinline__ typename E::x8 pack_x8(const f32x16 &x, int v0) {
+  typename E::x8 r;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) r[e] = (__bf16)x[v0 + e];
+  for (int e = 0; e < 8; ++e) r[e] = (typename E::elem)x[v0 + e];
   return r;
 }
 
-// Position of streamed row j (0..63 within a 64-row block) inside a transposed LDS row, chosen
-// so that the 8 rows one lane needs for a k-step are contiguous: swap bits 2 and 3 of j.
-__device__ __forceinline__ int tr_pos(int j) { return (j & ~12) | ((j & 8) >> 1) | ((j & 4) << 1); }
-
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
-  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-  bf16x2 r;
-  r.x = (__bf16)lo;
-  r.y = (__bf16)hi;
+template <class E> __device__ __forceinline__ uint32_t pack2(float lo, float hi) {
+  typedef typename E::elem x2 __attribute__((ext_vector_type(2)));
+  x2 r;
+  r.x = (typename E::elem)lo;
+  r.y = (typename E::elem)hi;
   return __builtin_bit_cast(uint32_t, r);
 }
+__device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) { return pack2<Bf16>(lo, hi); }
 
 // Transposing LDS read (ds_read_b64_tr_b16).  Within each block of 16 lanes, lane 4r + q supplies
 // the address of 4 consecutive bf16 M[r][4q..4q+3] of a 4 x 16 matrix; lane i of the block receives
@@ -63,23 +79,6 @@ __device__ __forceinline__ uint32_t pack2_bf16(float lo, float hi) {
 // column -- which is exactly what an A operand "rows = columns of X, k = rows of X" needs.
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
-
-// Per-lane element offset into a row-major LDS block with `stride` elements per row: lane 4r + q of
-// 16-lane block b addresses row 4 (b / 2) + r, columns 16 (b % 2) + 4q.
-__device__ __forceinline__ int tr_lane_offset(int lane, int stride) {
-  const int b = lane >> 4, r = (lane & 15) >> 2, q = lane & 3;
-  return (4 * (b >> 1) + r) * stride + 16 * (b & 1) + 4 * q;
-}
-
-// A operand for one 16-row k-step whose B operand came from pack_bf16x8: rows {4 half + 0..3} and
-// {8 + 4 half + 0..3} of the block at `p` (already offset by tr_lane_offset); `second` = 8 rows.
-__device__ __forceinline__ bf16x8 lds_read_tr8(const uint16_t *p, int second) {
-  typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
-  const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p));
-  const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(p + second));
-  const s16x8 r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, r);
-}
 
 // s_waitcnt vmcnt(0), visible to the compiler's wait-count bookkeeping (expcnt and lgkmcnt fields
 // left at their maxima: 7 << 4, 15 << 8).
@@ -141,9 +140,10 @@ __device__ __forceinline__ uint32_t swz_row_lane_off(int lane) {
   const int l32 = lane & 31, half = lane >> 5;
   return (uint32_t)(l32 * 256 + ((half ^ swz(l32)) << 4));
 }
-__device__ __forceinline__ bf16x8 swz_read_row(const uint16_t *blk, uint32_t lane_off, int ks, int row0) {
+template <class E>
+__device__ __forceinline__ typename E::x8 swz_read_row(const uint16_t *blk, uint32_t lane_off, int ks, int row0) {
   const uint32_t off = (lane_off ^ (uint32_t)(ks << 5)) + (uint32_t)row0 * 256u;
-  return as_bf16x8(*(const u32x4 *)((const char *)blk + off));
+  return as_x8<E>(*(const u32x4 *)((const char *)blk + off));
 }
 
 // Transposing reads from a swizzled block: byte offsets of this lane's two 8-byte reads (rows
@@ -158,32 +158,15 @@ __device__ __forceinline__ void swz_tr_lane_off(int lane, uint32_t (&off)[2]) {
     off[t] = (uint32_t)(j16 * 256 + ((ch ^ swz(j16)) << 4) + (q & 1) * 8);
   }
 }
-__device__ __forceinline__ bf16x8 swz_read_tr(const uint16_t *blk, const uint32_t (&lane_off)[2], int cb, int j0) {
+template <class E>
+__device__ __forceinline__ typename E::x8 swz_read_tr(const uint16_t *blk, const uint32_t (&lane_off)[2], int cb, int j0) {
   typedef s16x4 __attribute__((address_space(3))) * lds_ptr;
   const char *base = (const char *)blk + (uint32_t)j0 * 256u;
   const s16x4 a = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(base + (lane_off[0] ^ (uint32_t)(cb << 6))));
   const s16x4 b = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_ptr)(base + (lane_off[1] ^ (uint32_t)(cb << 6))));
   const s16x8 r = __builtin_shufflevector(a, b, 0, 1, 2, 3, 4, 5, 6, 7);
-  return __builtin_bit_cast(bf16x8, r);
+  return __builtin_bit_cast(typename E::x8, r);
 }
-
-// Cooperative block copy HBM -> registers -> swizzled LDS block for a workgroup of kThreads
-// threads: a [kRows][128] bf16 block is kRows * 16 chunks, kRows * 16 / kThreads per thread.
-template <int kRows, int kThreads>
-struct BlockCopy {
-  static constexpr int kPer = kRows * 16 / kThreads;
-  u32x4 r[kPer];
-  // byte offset (inside the block, head included) of chunk p of this thread in global memory
-  __device__ __forceinline__ static uint32_t global_off(int p, size_t row_bytes, int head) {
-    const int q = threadIdx.x + kThreads * p;
-    return (uint32_t)((q >> 4) * row_bytes + (size_t)head * kD * 2 + (q & 15) * 16);
-  }
-  __device__ __forceinline__ static uint32_t lds_off(int p) {
-    const int q = threadIdx.x + kThreads * p;
-    const int j = q >> 4, ch = q & 15;
-    return (uint32_t)(j * 256 + ((ch ^ swz(j)) << 4));
-  }
-};
 
 // 16-byte global load with a validity guard (zero when !ok)
 __device__ __forceinline__ u32x4 ldg16(const uint16_t *p, bool ok) {
@@ -191,55 +174,35 @@ __device__ __forceinline__ u32x4 ldg16(const uint16_t *p, bool ok) {
   return ok ? *(const u32x4 *)p : z;
 }
 
-// Cooperative copy of a [64 x 128] bf16 block of a [N, H, 128] tensor into LDS, row-major with
-// a row stride of `stride` elements.  256 threads, 4 x 16 B each.  Rows >= N read as zero.
-__device__ __forceinline__ void load_rows_to_lds(const uint16_t *__restrict__ X, int row0, int N,
-                                                 int H, int head, uint16_t *lds, int stride) {
+// This lane's row of a [N, H, d] tensor as kKs operand fragments: fragment ks holds columns
+// 16 ks + 8 half .. + 7; columns at or beyond d read as zeros.
+template <class E, int kKs>
+__device__ __forceinline__ void load_row_fragments(const uint16_t *row, int d, int half, typename E::x8 (&f)[kKs]) {
 #pragma unroll
-  for (int p = 0; p < 4; ++p) {
-    const int q = threadIdx.x + 256 * p;
-    const int r = q >> 4, c16 = q & 15;
-    const int row = row0 + r;
-    u32x4 x = ldg16(X + ((size_t)row * H + head) * kD + c16 * 8, row < N);
-    *(u32x4 *)(lds + r * stride + c16 * 8) = x;
+  for (int ks = 0; ks < kKs; ++ks) {
+    const int c = ks * 16 + half * 8;
+    f[ks] = as_x8<E>(ldg16(row + c, c < d));
   }
 }
 
-// Same block, but stored transposed: lds[c * stride + tr_pos(j)] = X[row0 + j][c].  Each thread
-// loads 4 consecutive rows x 8 columns and writes eight 8-byte groups (4 rows of one column).
-__device__ __forceinline__ void load_rows_to_lds_transposed(const uint16_t *__restrict__ X, int row0,
-                                                            int N, int H, int head, uint16_t *lds,
-                                                            int stride) {
-  const int cc = threadIdx.x & 15, jg = threadIdx.x >> 4;
-  u32x4 x[4];
-#pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int row = row0 + 4 * jg + r;
-    x[r] = ldg16(X + ((size_t)row * H + head) * kD + cc * 8, row < N);
-  }
-  const int pos = tr_pos(4 * jg);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int w = e >> 1;
-    u32x2 o;
-    if (e & 1) {
-      o.x = (x[0][w] >> 16) | (x[1][w] & 0xffff0000u);
-      o.y = (x[2][w] >> 16) | (x[3][w] & 0xffff0000u);
-    } else {
-      o.x = (x[0][w] & 0xffffu) | (x[1][w] << 16);
-      o.y = (x[2][w] & 0xffffu) | (x[3][w] << 16);
-    }
-    *(u32x2 *)(lds + (cc * 8 + e) * stride + pos) = o;
-  }
+// Per-lane part of the HBM -> LDS copy of swizzled blocks (see the forward kernel): the lane that
+// lands at chunk position lane % 16 of LDS row `row` fetches global chunk (lane % 16) ^ swz(row) of
+// that row and head.  A chunk at or beyond the head_dim must bring zeros: dma_lane_ok is false for
+// it and the copy then uses the offset kPastEnd (beyond every buffer) instead.
+__device__ __forceinline__ uint32_t dma_lane_offset(int lane, int row, size_t row_bytes, int head, int d) {
+  const int gc = (lane & 15) ^ swz(row);
+  return (uint32_t)(row * row_bytes + (size_t)head * d * 2 + gc * 16);
 }
+__device__ __forceinline__ bool dma_lane_ok(int lane, int row, int d) { return (((lane & 15) ^ swz(row)) * 8) < d; }
 
 // Epilogue shared by all three kernels: a wave holds a transposed result tile
-//   acc[cb][v] = R[row = lane % 32][col = 32 cb + acc_row(v, half)],   32 rows x 128 cols,
-// multiplies row `lane % 32` by `mul`, and writes rows 0..nrows-1 to out[(row0 + row) * H + head]
-// (a [N, H, 128] tensor) with coalesced stores.  The tile is staged through LDS in two halves of
-// 64 columns; `stage` is this wave's private [32][kStageStride] float buffer, so only wave-level
-// ordering is needed here (LDS operations of one wave execute in order).  The caller must have
-// passed a workgroup barrier after the last use of the memory `stage` overlays.
+//   acc[cb][v] = R[row = lane % 32][col = 32 cb + acc_row(v, half)],   32 rows x 32 kCb cols,
+// multiplies row `lane % 32` by `mul`, and writes columns < d of rows 0..nrows-1 to
+// out[(row0 + row) * H + head] (a [N, H, d] tensor) with coalesced stores.  The tile is staged
+// through LDS in halves of 64 columns; `stage` is this wave's private [32][kStageStride] float
+// buffer, so only wave-level ordering is needed here (LDS operations of one wave execute in
+// order).  The caller must have passed a workgroup barrier after the last use of the memory `stage`
+// overlays.  EOut = float stores fp32, otherwise the 16-bit element type of EOut.
 constexpr int kStageStride = 64 + 4;
 constexpr int kStageFloatsPerWave = 32 * kStageStride;
 
@@ -249,16 +212,26 @@ __device__ __forceinline__ void wave_lds_fence() {
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <bool kF32Out>
-__device__ __forceinline__ void store_transposed_tile(const f32x16 (&acc)[4], float mul, float *stage,
+template <class EOut> struct is_f32_out { static constexpr bool value = false; };
+template <> struct is_f32_out<float> { static constexpr bool value = true; };
+template <class EOut, bool kF32 = is_f32_out<EOut>::value> struct OutPack {
+  static __device__ __forceinline__ uint32_t two(float lo, float hi) { return pack2<EOut>(lo, hi); }
+};
+template <class EOut> struct OutPack<EOut, true> {
+  static __device__ __forceinline__ uint32_t two(float, float) { return 0u; }
+};
+
+template <class EOut, int kCb>
+__device__ __forceinline__ void store_transposed_tile(const f32x16 (&acc)[kCb], float mul, float *stage,
                                                       void *out, long long row0, int nrows, int H,
-                                                      int head) {
+                                                      int head, int d) {
   const int lane = threadIdx.x & 63, l32 = lane & 31, half = lane >> 5;
 #pragma unroll
-  for (int p = 0; p < 2; ++p) {
+  for (int p = 0; p < (kCb + 1) / 2; ++p) {
     wave_lds_fence();  // the reads of the previous half (or tile) are done before it is overwritten
 #pragma unroll
-    for (int cc = 0; cc < 2; ++cc)
+    for (int cc = 0; cc < 2; ++cc) {
+      if (2 * p + cc >= kCb) continue;
 #pragma unroll
       for (int q4 = 0; q4 < 4; ++q4) {
         f32x4 w;
@@ -266,19 +239,21 @@ __device__ __forceinline__ void store_transposed_tile(const f32x16 (&acc)[4], fl
         for (int b = 0; b < 4; ++b) w[b] = acc[2 * p + cc][4 * q4 + b] * mul;
         *(f32x4 *)(stage + l32 * kStageStride + cc * 32 + q4 * 8 + half * 4) = w;
       }
+    }
     wave_lds_fence();
 #pragma unroll
     for (int it = 0; it < 8; ++it) {
       const int rr = it * 4 + (lane >> 4), c4 = lane & 15;
-      if (rr < nrows) {
+      const int col = p * 64 + c4 * 4;
+      if (rr < nrows && col < d && col < kCb * 32) {
         const f32x4 x = *(const f32x4 *)(stage + rr * kStageStride + c4 * 4);
-        const size_t off = ((size_t)(row0 + rr) * H + head) * kD + p * 64 + c4 * 4;
-        if (kF32Out) {
+        const size_t off = ((size_t)(row0 + rr) * H + head) * d + col;
+        if (is_f32_out<EOut>::value) {
           *(f32x4 *)((float *)out + off) = x;
         } else {
           u32x2 w;
-          w.x = pack2_bf16(x[0], x[1]);
-          w.y = pack2_bf16(x[2], x[3]);
+          w.x = OutPack<EOut>::two(x[0], x[1]);
+          w.y = OutPack<EOut>::two(x[2], x[3]);
           *(u32x2 *)((uint16_t *)out + off) = w;
         }
       }

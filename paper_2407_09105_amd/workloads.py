@@ -111,6 +111,11 @@ def round_to_bf16(x: np.ndarray) -> np.ndarray:
     return r.view(np.float32)
 
 
+def round_to_f16(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest IEEE half (ties to even); returned as float32."""
+    return np.ascontiguousarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
 def bf16_bits(x: np.ndarray) -> np.ndarray:
     """uint16 bit patterns of float32 values that are exactly bf16."""
     u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
@@ -183,6 +188,8 @@ def make_custom(lengths_per_row: List[List[int]], hq: int, hkv: int, d: int, dty
     arrs = [rng.standard_normal(s, dtype=np.float32) for s in shapes]
     if dtype == "bf16":
         arrs = [round_to_bf16(a) for a in arrs]
+    elif dtype == "f16":
+        arrs = [round_to_f16(a) for a in arrs]
     w = Workload(cfg, seed, [list(r) for r in lengths_per_row], pos, *arrs, stats=length_stats(lengths_per_row))
     return w
 

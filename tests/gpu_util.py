@@ -15,7 +15,9 @@ BF16_MAX_ABS, BF16_REL_L2, F32_REL_L2 = 2e-2, 5e-3, 1e-4
 
 def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
     t = torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
-    return t.to(torch.bfloat16) if dtype == "bf16" else t     # exact: values are already bf16
+    if dtype == "bf16":
+        return t.to(torch.bfloat16)                            # exact: values are already bf16
+    return t.to(torch.float16) if dtype == "f16" else t        # exact likewise
 
 
 def rel_l2(x: np.ndarray, ref: np.ndarray) -> float:
@@ -67,7 +69,7 @@ def assert_close(got: dict, ref: dict, dtype: str, what=("O", "dQ", "dK", "dV"),
     errs["LSE"] = (max_abs(got["LSE"], ref["LSE"]), 0.0)
     for key in what:
         ma, rl = errs[key]
-        if dtype == "bf16":
+        if dtype in ("bf16", "f16"):   # the 16-bit paths share the bar (fp16 rounds P and dS finer than bf16)
             assert rl <= BF16_REL_L2, (key, errs)
             if key in bf16_stored:
                 excess = np.abs(got[key] - ref[key]) - (BF16_MAX_ABS + np.abs(ref[key]) / 256.0)
@@ -76,5 +78,5 @@ def assert_close(got: dict, ref: dict, dtype: str, what=("O", "dQ", "dK", "dV"),
                 assert ma <= BF16_MAX_ABS, (key, errs)
         else:
             assert rl <= F32_REL_L2, (key, errs)
-    assert errs["LSE"][0] <= (1e-3 if dtype == "bf16" else 1e-5), errs
+    assert errs["LSE"][0] <= (1e-3 if dtype in ("bf16", "f16") else 1e-5), errs
     return errs

@@ -15,7 +15,7 @@ def _parity(w, grad_dtype=None, scale=0.0):
     got = run_gpu(w, grad_dtype=grad_dtype, scale=scale)
     ref = run_oracle(w, scale=None if scale == 0.0 else scale)
     assert_seg_equal(got["seg"], ref["seg"])
-    stored = ("dQ", "dK", "dV") if grad_dtype == torch.bfloat16 else ()
+    stored = ("dQ", "dK", "dV") if grad_dtype in (torch.bfloat16, torch.float16) else ()
     errs = assert_close(got, ref, w.cfg.dtype, bf16_stored=stored)
     print("   errors (max-abs, rel-L2):", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in errs.items()}, flush=True)
     return got, ref
@@ -38,8 +38,10 @@ def test_fp32_explicit_scale():
     _parity(wl.make_custom([[9, 3, 20]], 2, 2, 32, "f32", seed=6), scale=0.21)
 
 
-def test_bf16_generic_other_head_dim():
-    _parity(wl.make_custom([[40, 7, 81]], 4, 2, 64, "bf16", seed=7), grad_dtype=torch.float32)
+@pytest.mark.parametrize("d,dtype", [(20, "bf16"), (256, "bf16"), (36, "f16"), (256, "f16")])
+def test_generic_16bit_other_head_dims(d, dtype):
+    # head dims the MFMA kernels do not take (not a multiple of 8, or above 128): plain kernels
+    _parity(wl.make_custom([[40, 7, 81]], 4, 2, d, dtype, seed=7), grad_dtype=torch.float32)
 
 
 MFMA_CASES = [
@@ -62,6 +64,30 @@ def test_bf16_mfma_fp32_grads(lengths, hq, hkv):
 @pytest.mark.parametrize("lengths,hq,hkv", [MFMA_CASES[3], MFMA_CASES[4]])
 def test_bf16_mfma_bf16_grads(lengths, hq, hkv):
     _parity(wl.make_custom(lengths, hq, hkv, 128, "bf16", seed=12), grad_dtype=torch.bfloat16)
+
+
+# Head dims and element types of the model families the paper lists (Section 4): 64, 80, 96, 128;
+# bf16 and fp16 checkpoints; multi-query attention (one KV head).  d < 128 runs the 64 / 96 / 128
+# instantiations with zero columns supplied on the fly.
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("d", [64, 80, 96, 128, 8, 72, 112])
+def test_mfma_head_dims_and_dtypes(d, dtype):
+    if d == 128 and dtype == "bf16":
+        pytest.skip("covered above")
+    w = wl.make_custom([[300, 45, 1, 1, 200, 93]], 4, 2, d, dtype, seed=20 + d)
+    _parity(w, grad_dtype=torch.float32)
+
+
+@pytest.mark.parametrize("d,dtype", [(64, "bf16"), (128, "f16"), (80, "f16")])
+def test_mfma_16bit_grads_and_ragged_rows(d, dtype):
+    w = wl.make_custom([[100, 219], [319], [1] * 319], 2, 2, d, dtype, seed=31)
+    _parity(w, grad_dtype=torch.bfloat16 if dtype == "bf16" else torch.float16)
+
+
+def test_multi_query_attention():
+    # one KV head shared by every query head (the falcon-style models of the paper's list)
+    _parity(wl.make_custom([[513, 31, 480]], 8, 1, 64, "bf16", seed=33), grad_dtype=torch.float32)
+    _parity(wl.make_custom([[200, 120]], 6, 1, 128, "f16", seed=34), grad_dtype=torch.float32)
 
 
 def test_bf16_mfma_explicit_scale():
