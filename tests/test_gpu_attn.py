@@ -100,3 +100,25 @@ def test_bwd_is_deterministic():
     b = run_gpu(w, grad_dtype=torch.float32)
     for key in ("O", "LSE", "dQ", "dK", "dV"):
         assert np.array_equal(a[key], b[key]), key
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes(seed):
+    # seeded random rows / row lengths / example lengths / head counts / head dims / element types:
+    # tile edges, ragged tails and grouped heads in combinations the hand-picked cases do not list
+    rng = np.random.default_rng(1000 + seed)
+    R = int(rng.integers(1, 4))
+    T = int(rng.integers(1, 700))
+    rows = []
+    for _ in range(R):
+        row, left = [], T
+        while left > 0:
+            L = int(min(left, rng.integers(1, max(2, int(rng.choice([8, 70, 300, 700]))))))
+            row.append(L)
+            left -= L
+        rows.append(row)
+    hkv = int(rng.choice([1, 2, 3]))
+    hq = hkv * int(rng.choice([1, 2, 5]))
+    d = int(rng.choice([64, 96, 128, 40]))
+    dtype = str(rng.choice(["bf16", "f16"]))
+    _parity(wl.make_custom(rows, hq, hkv, d, dtype, seed=2000 + seed), grad_dtype=torch.float32)
