@@ -16,9 +16,20 @@ namespace {
 
 constexpr int kPerThread = kScanChunk / kScanThreads;  // 8 consecutive tokens per thread
 
+// Start flags of the kPerThread consecutive tokens from `base`.  The ids are loaded
+// unconditionally (index clamped into the stream) before any of them is looked at: loads under a
+// condition would be issued one at a time, each waiting for the one before.
 template <typename IdT>
-__device__ __forceinline__ bool is_start(const IdT *pos, int t, int T) {
-  return (t % T == 0) || (pos[t] == 0);
+__device__ __forceinline__ void start_flags(const IdT *pos, int base, int N, int T, bool (&flag)[kPerThread]) {
+  IdT id[kPerThread];
+#pragma unroll
+  for (int e = 0; e < kPerThread; ++e) id[e] = pos[min(base + e, N - 1)];
+  int r = base % T;  // position inside the packed row, advanced without further divisions
+#pragma unroll
+  for (int e = 0; e < kPerThread; ++e) {
+    flag[e] = base + e < N && (id[e] == 0 || r == 0);
+    if (++r == T) r = 0;
+  }
 }
 
 // ---- block-wide scans over kScanThreads values (LDS, Hillis-Steele per wave + wave carries) ----
@@ -57,11 +68,13 @@ __global__ void __launch_bounds__(kScanThreads)
 scan_aggregate_kernel(const IdT *__restrict__ pos, int N, int T, int32_t *__restrict__ agg) {
   __shared__ int s_cnt[kScanThreads / 64], s_last[kScanThreads / 64], s_first[kScanThreads / 64];
   const int base = blockIdx.x * kScanChunk + threadIdx.x * kPerThread;
+  bool flag[kPerThread];
+  start_flags(pos, base, N, T, flag);
   int cnt = 0, last = -1, first = N;
 #pragma unroll
   for (int e = 0; e < kPerThread; ++e) {
     const int t = base + e;
-    if (t < N && is_start(pos, t, T)) {
+    if (flag[e]) {
       ++cnt;
       last = t;
       first = min(first, t);
@@ -136,11 +149,11 @@ scan_finalize_kernel(const IdT *__restrict__ pos, int N, int T, const int32_t *_
   __shared__ int s_cnt[kScanThreads / 64], s_last[kScanThreads / 64], s_first[kScanThreads / 64];
   const int base = blockIdx.x * kScanChunk + threadIdx.x * kPerThread;
   bool flag[kPerThread];
+  start_flags(pos, base, N, T, flag);
   int cnt = 0, last = -1, first = N;
 #pragma unroll
   for (int e = 0; e < kPerThread; ++e) {
     const int t = base + e;
-    flag[e] = (t < N) && is_start(pos, t, T);
     if (flag[e]) { ++cnt; last = t; first = min(first, t); }
   }
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -237,8 +250,8 @@ tile_rank_kernel(const unsigned long long *__restrict__ cost_q, const unsigned l
 }
 
 // ---- two-launch path for streams of up to kOnePassMaxChunks chunks --------------------------------
-// Launch 1: every chunk's workgroup derives its own carries by reading the ids of the chunks before
-// it (count and last start) and after it (first start) -- redundant reads that stay in L2, in
+// Launch 1: every chunk's workgroup derives its own carries by reading the ids of all other chunks
+// (count and last start before it, first start after it) -- redundant reads that stay in L2, in
 // exchange for no inter-workgroup dependency and no separate carry kernel.  Launch 2: sort keys of
 // all tiles into LDS, ranks of this workgroup's tiles, and max_seqlen from the per-chunk maxima.
 constexpr int kOnePassMaxChunks = 4;  // 8192 tokens: beyond that the redundant reads cost more than two launches
@@ -254,48 +267,55 @@ scan_onepass_kernel(const IdT *__restrict__ pos, int N, int T, int32_t *__restri
   __shared__ int c_cnt, c_last, c_first;
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
   const int chunk0 = blockIdx.x * kScanChunk;
-  // carries from the tokens before this chunk
+  // this thread's own tokens: their loads go out together with the sweep's below
+  const int base = chunk0 + threadIdx.x * kPerThread;
+  bool flag[kPerThread];
+  start_flags(pos, base, N, T, flag);
+  // Carries from the rest of the stream in one sweep: every id outside this chunk is read once, all
+  // loads of a thread issued together (the stream has at most kOnePassMaxChunks chunks), giving the
+  // number of starts and the last start before the chunk and the first start after it.
   {
-    int cnt = 0, last = -1;
-    for (int t = threadIdx.x; t < chunk0; t += kScanThreads)
-      if (is_start(pos, t, T)) { ++cnt; last = t; }
+    constexpr int kSweep = kOnePassMaxChunks * kScanChunk / kScanThreads;
+    const int chunk1 = chunk0 + kScanChunk;
+    IdT id[kSweep];  // unconditional loads (index clamped), so that they are all in flight together
+#pragma unroll
+    for (int u = 0; u < kSweep; ++u) id[u] = pos[min(u * kScanThreads + (int)threadIdx.x, N - 1)];
+    int cnt = 0, last = -1, first = N;
+    int r = threadIdx.x % T;  // position inside the packed row, advanced without further divisions
+    const int step = kScanThreads % T;
+#pragma unroll
+    for (int u = 0; u < kSweep; ++u) {
+      const int t = u * kScanThreads + threadIdx.x;
+      if (t < N && (t < chunk0 || t >= chunk1) && (id[u] == 0 || r == 0)) {
+        if (t < chunk0) { ++cnt; last = t; } else first = min(first, t);
+      }
+      r += step;
+      if (r >= T) r -= T;
+    }
     for (int o = 32; o > 0; o >>= 1) {
       cnt += __shfl_xor(cnt, o, 64);
       last = max(last, __shfl_xor(last, o, 64));
+      first = min(first, __shfl_xor(first, o, 64));
     }
-    if (lane == 0) { s_cnt[w] = cnt; s_last[w] = last; }
+    if (lane == 0) { s_cnt[w] = cnt; s_last[w] = last; s_first[w] = first; }
     __syncthreads();
     if (threadIdx.x == 0) {
-      for (int i = 1; i < kScanThreads / 64; ++i) { cnt += s_cnt[i]; last = max(last, s_last[i]); }
+      for (int i = 1; i < kScanThreads / 64; ++i) {
+        cnt += s_cnt[i];
+        last = max(last, s_last[i]);
+        first = min(first, s_first[i]);
+      }
       c_cnt = cnt;
       c_last = last;
+      c_first = first;
     }
-  }
-  // first start after this chunk: look ahead one chunk at a time (the next row start bounds it)
-  {
-    int found = N;
-    for (int b0 = chunk0 + kScanChunk; b0 < N && found == N; b0 += kScanChunk) {
-      int first = N;
-      for (int t = b0 + threadIdx.x; t < min(b0 + kScanChunk, N); t += kScanThreads)
-        if (is_start(pos, t, T)) first = min(first, t);
-      for (int o = 32; o > 0; o >>= 1) first = min(first, __shfl_xor(first, o, 64));
-      __syncthreads();  // s_first free (previous round consumed)
-      if (lane == 0) s_first[w] = first;
-      __syncthreads();
-      for (int i = 0; i < kScanThreads / 64; ++i) found = min(found, s_first[i]);  // same value in every thread
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) c_first = found;
   }
   __syncthreads();
   // local scan, as in scan_finalize_kernel
-  const int base = chunk0 + threadIdx.x * kPerThread;
-  bool flag[kPerThread];
   int cnt = 0, last = -1, first = N;
 #pragma unroll
   for (int e = 0; e < kPerThread; ++e) {
     const int t = base + e;
-    flag[e] = (t < N) && is_start(pos, t, T);
     if (flag[e]) { ++cnt; last = t; first = min(first, t); }
   }
   const int icnt = wave_incl_add(cnt), ilast = wave_incl_max(last), sfirst = wave_suffix_min(first);
