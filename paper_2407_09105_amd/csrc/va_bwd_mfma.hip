@@ -121,13 +121,13 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
       for (int sb = 0; sb < 2; ++sb) {
         const int jl = j0 + sb * 32;
         if (jl > iw1 || jl + 31 < ss_min) continue;  // wave-uniform
-        f32x16 s, dp;
+        f32x16 s, dp;  // dP accumulates onto -D of this lane's query row
 #pragma unroll
-        for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = 0.f; }
+        for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = -dl; }
 #pragma unroll
         for (int ks = 0; ks < kKs; ++ks) {
           s = mfma32(swz_read_row<E>(Kb, row_lane, ks, sb * 32), qf[ks], s);     // S^T  = K Q^T
-          dp = mfma32(swz_read_row<E>(Vb, row_lane, ks, sb * 32), gf[ks], dp);   // dP^T = V dO^T
+          dp = mfma32(swz_read_row<E>(Vb, row_lane, ks, sb * 32), gf[ks], dp);   // dP^T - D = V dO^T - D
         }
         const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
 #pragma unroll
@@ -137,7 +137,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
             const int j = jl + acc_row(v, half);
             if (j < ss_i || j > i_abs) p = 0.f;
           }
-          s[v] = p * (dp[v] - dl);  // dS^T
+          s[v] = p * dp[v];  // dS^T
         }
 #pragma unroll
         for (int s2 = 0; s2 < 2; ++s2) {
