@@ -71,7 +71,7 @@ class GpuRun:
         b.varlen_attn_fwd(self.q, self.k, self.v, self.seg, out=self.o, lse=self.lse)
         if ev: ev[2].record()
         if ev:
-            for i, stage in enumerate((b.STAGE_D, b.STAGE_DKDV, b.STAGE_DQ)):
+            for i, stage in enumerate((b.STAGE_DQ, b.STAGE_DKDV)):   # the order of the full backward
                 b.varlen_attn_bwd(self.do, self.q, self.k, self.v, self.o, self.lse, self.seg, dq=self.dq,
                                   dk=self.dk, dv=self.dv, workspace=self.ws, stages=stage)
                 ev[3 + i].record()
@@ -86,7 +86,7 @@ def timed(torch, run, steps, warmup, with_events=True):
     on the stream the kernels are launched on (torch's current stream, whose handle the binding passes)."""
     for _ in range(warmup):
         run.step()
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(6)] for _ in range(steps)] if with_events else None
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(steps)] if with_events else None
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(steps):
@@ -95,7 +95,7 @@ def timed(torch, run, steps, warmup, with_events=True):
     ms = (time.perf_counter() - t0) * 1e3 / steps
     stages = {}
     if evs:
-        names = ["pack", "fwd", "bwd_D", "bwd_dKdV", "bwd_dQ"]
+        names = ["pack", "fwd", "bwd_dQ", "bwd_dKdV"]   # the dQ kernel also forms D = rowsum(dO * O)
         for i, n in enumerate(names):
             stages[n] = float(np.mean([e[i].elapsed_time(e[i + 1]) for e in evs]))
     return ms, stages

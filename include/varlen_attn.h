@@ -173,10 +173,14 @@ va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const
                              size_t workspace_bytes, void *stream);
 
 /*
- * The backward is three kernels: D = rowsum(dO * O), then dK/dV, then dQ.  This variant runs only
- * the ones selected by `stages` (an OR of the flags below), so that a caller can time them one by
- * one with events on `stream`.  Running all three flags in order gives exactly va_varlen_attn_bwd;
- * VA_STAGE_DKDV and VA_STAGE_DQ read the D that an earlier VA_STAGE_D call left in `workspace`.
+ * The backward in parts, so that a caller can time its kernels one by one with events on `stream`:
+ * `stages` is an OR of the flags below.
+ *   VA_STAGE_D    D = rowsum(dO * O) into `workspace`.
+ *   VA_STAGE_DQ   dQ.  The plain kernels read D from `workspace`; the MFMA kernel forms D for its
+ *                 own rows and (re)writes `workspace` with it.
+ *   VA_STAGE_DKDV dK, dV; reads the D that an earlier VA_STAGE_D or VA_STAGE_DQ left in `workspace`.
+ * Within one call the order is D (skipped when the MFMA dQ kernel makes it redundant), dQ, dK/dV;
+ * all three flags give exactly va_varlen_attn_bwd.
  * Arguments, validation and errors as va_varlen_attn_bwd; stages == 0 or unknown bits: VA_ERR_UNSUPPORTED.
  */
 #define VA_STAGE_D 1u

@@ -181,11 +181,13 @@ va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K
   float *delta = (float *)workspace;
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = hipSuccess;
-  if (stages & VA_STAGE_D) e = va::launch_delta(dO, O, delta, N, hq, d, dt, st);
+  const bool mfma = use_mfma(dt, d);
+  // the MFMA dQ kernel forms D itself (and stores it for the dK/dV kernel, which it precedes)
+  if ((stages & VA_STAGE_D) && !(mfma && (stages & VA_STAGE_DQ))) e = va::launch_delta(dO, O, delta, N, hq, d, dt, st);
   if (e != hipSuccess) return VA_ERR_HIP;
   if (stages & (VA_STAGE_DKDV | VA_STAGE_DQ)) {
-    if (use_mfma(dt, d))
-      e = va::launch_mfma_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, rows, tokens_per_row, hq,
+    if (mfma)
+      e = va::launch_mfma_bwd(dO, Q, K, V, O, LSE, delta, dQ, dK, dV, grad_dt, *seg, rows, tokens_per_row, hq,
                               hkv, d, dt, scale, st, stages);
     else
       e = va::launch_generic_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, N, hq, hkv, d, dt, scale,

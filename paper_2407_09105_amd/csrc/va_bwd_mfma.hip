@@ -8,7 +8,8 @@
 //
 // Two kernels, no atomics, bitwise reproducible:
 //   dq_mfma_kernel   : workgroup = (128-query tile, query head); streams K/V blocks of 64 rows.
-//                      Lane owns a query row: S^T = K Q^T, dP^T = V dO^T, dQ^T += K^T dS^T.
+//                      Lane owns a query row: S^T = K Q^T, dP^T = V dO^T, dQ^T += K^T dS^T.  It also
+//                      forms D for its rows and stores it for the other kernel, so it runs first.
 //   dkdv_mfma_kernel : workgroup = (128-key tile, KV head); streams Q/dO blocks of 64 rows of every
 //                      query head of the group.  Lane owns a key row: S = Q K^T, dP = dO V^T,
 //                      dV^T += dO^T P, dK^T += Q^T dS; the dV and the dK halves run on different waves.
@@ -35,7 +36,8 @@ template <class E, class EOut, int kDh>
 __global__ void __launch_bounds__(256, 2)
 dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
                const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
-               const float *__restrict__ LSE, const float *__restrict__ delta, void *__restrict__ dQ,
+               const uint16_t *__restrict__ O, const float *__restrict__ LSE,
+               float *__restrict__ delta, void *__restrict__ dQ,
                const int32_t *__restrict__ seg_start, const int32_t *__restrict__ q_tile_order, int N,
                int T, int tiles_per_row, int hq, int hkv, int d, float scale_log2, float scale) {
   constexpr int kKs = kDh / 16, kCb = kDh / 32;
@@ -74,7 +76,19 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   load_row_fragments<E, kKs>(Q + ((size_t)i_ld * hq + h) * d, d, half, qf);
   load_row_fragments<E, kKs>(dO + ((size_t)i_ld * hq + h) * d, d, half, gf);
   const float lse2 = LSE[(size_t)h * N + i_ld] * kLog2e;
-  const float dl = delta[(size_t)h * N + i_ld];
+  // D = dO . O of this lane's query row, computed here (each lane of a pair holds half of the row)
+  // and left in `delta` for the dK/dV kernel, which runs after this one
+  float dl = 0.f;
+  {
+    x8 of[kKs];
+    load_row_fragments<E, kKs>(O + ((size_t)i_ld * hq + h) * d, d, half, of);
+#pragma unroll
+    for (int ks = 0; ks < kKs; ++ks)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) dl = fmaf((float)gf[ks][e], (float)of[ks][e], dl);
+    dl = pair_sum(dl);
+    if (row_ok && half == 0) delta[(size_t)h * N + i_abs] = dl;
+  }
 
   f32x16 acc[kCb];
 #pragma unroll
@@ -365,18 +379,18 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 
 template <class E, class EOut, int kDh>
 static void launch_bwd_t(const uint16_t *g, const uint16_t *q, const uint16_t *k, const uint16_t *v,
-                         const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
+                         const uint16_t *o, const float *LSE, float *delta, void *dQ, void *dK, void *dV,
                          const va_segments &seg, int N, int T, int tiles_per_row, int hq, int hkv, int d,
                          float scale, unsigned gq, unsigned gkv, hipStream_t stream, unsigned stages) {
   const float scale_log2 = scale * kLog2e;
+  if (stages & VA_STAGE_DQ)  // first: it also produces D for the dK/dV kernel
+    dq_mfma_kernel<E, EOut, kDh><<<gq, 256, 0, stream>>>(g, q, k, v, o, LSE, delta, dQ, seg.seg_start,
+                                                         seg.q_tile_order, N, T, tiles_per_row, hq, hkv, d,
+                                                         scale_log2, scale);
   if (stages & VA_STAGE_DKDV)
     dkdv_mfma_kernel<E, EOut, kDh><<<gkv, kDkdvThreads, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
                                                                      seg.kv_tile_order, N, T, tiles_per_row, hq,
                                                                      hkv, d, scale_log2, scale);
-  if (stages & VA_STAGE_DQ)
-    dq_mfma_kernel<E, EOut, kDh><<<gq, 256, 0, stream>>>(g, q, k, v, LSE, delta, dQ, seg.seg_start,
-                                                         seg.q_tile_order, N, T, tiles_per_row, hq, hkv, d,
-                                                         scale_log2, scale);
 }
 
 template <class E, class EOut, class... A>
@@ -386,8 +400,8 @@ static void launch_bwd_d(int d, A... a) {
   else launch_bwd_t<E, EOut, 128>(a...);
 }
 
-hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const void *V,
-                           const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
+hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const void *V, const void *O,
+                           const float *LSE, float *delta, void *dQ, void *dK, void *dV,
                            va_dtype grad_dt, const va_segments &seg, int rows, int T, int hq,
                            int hkv, int d, va_dtype dt, float scale, hipStream_t stream, unsigned stages) {
   const int tiles_per_row = ceil_div(T, VA_TILE);
@@ -395,21 +409,21 @@ hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const v
   if (ntiles * hq > 0x7fffffffll) return hipErrorInvalidValue;
   const int N = rows * T;
   const uint16_t *q = (const uint16_t *)Q, *k = (const uint16_t *)K, *v = (const uint16_t *)V,
-                 *g = (const uint16_t *)dO;
+                 *g = (const uint16_t *)dO, *o = (const uint16_t *)O;
   const unsigned gq = (unsigned)(ntiles * hq), gkv = (unsigned)(ntiles * hkv);
   if (dt == VA_F16) {
     if (grad_dt == VA_F32)
-      launch_bwd_d<F16, float>(d, g, q, k, v, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
+      launch_bwd_d<F16, float>(d, g, q, k, v, o, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
                                gq, gkv, stream, stages);
     else
-      launch_bwd_d<F16, F16>(d, g, q, k, v, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
+      launch_bwd_d<F16, F16>(d, g, q, k, v, o, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
                              gq, gkv, stream, stages);
   } else {
     if (grad_dt == VA_F32)
-      launch_bwd_d<Bf16, float>(d, g, q, k, v, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
+      launch_bwd_d<Bf16, float>(d, g, q, k, v, o, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
                                 gq, gkv, stream, stages);
     else
-      launch_bwd_d<Bf16, Bf16>(d, g, q, k, v, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
+      launch_bwd_d<Bf16, Bf16>(d, g, q, k, v, o, LSE, delta, dQ, dK, dV, seg, N, T, tiles_per_row, hq, hkv, d, scale,
                                gq, gkv, stream, stages);
   }
   return hipGetLastError();

@@ -43,8 +43,8 @@ hipError_t launch_generic_bwd(const void *dO, const void *Q, const void *K, cons
 hipError_t launch_mfma_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
                            const va_segments &seg, int rows, int T, int hq, int hkv, int d, va_dtype dt,
                            float scale, hipStream_t stream);
-hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const void *V,
-                           const float *LSE, const float *delta, void *dQ, void *dK, void *dV,
+hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const void *V, const void *O,
+                           const float *LSE, float *delta, void *dQ, void *dK, void *dV,
                            va_dtype grad_dt, const va_segments &seg, int rows, int T, int hq,
                            int hkv, int d, va_dtype dt, float scale, hipStream_t stream, unsigned stages);
 
