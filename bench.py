@@ -36,7 +36,8 @@ def parse_args():
     ap.add_argument("--config", type=int, default=2, help="workload (index into the config table, 2..5)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-padded", action="store_true")
-    ap.add_argument("--no-extras", action="store_true", help="skip the no-position-id and collator timings")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="only the timed step: skip measured peaks, cold-cache, no-position-id, collator and rotary timings")
     ap.add_argument("--packers", action="store_true",
                     help="also time the step on packs made by the paper's samplers from one example pool")
     ap.add_argument("--cpu-heads", type=int, default=0, help="query heads in the CPU-oracle sample (0 = auto)")
@@ -372,12 +373,12 @@ def main():
             "tokens_per_s": cfg.n_tokens / (pms * 1e-3), "packing_gain": pms / ms_plain,
         }
         del prun
-    out["measured_peaks"] = measured_peaks(torch, binding)
-    out["frac_measured_mfma_peak"] = value / out["measured_peaks"]["mfma_bf16_TFLOPs"]
-    cold = cold_cache_ms(torch, binding, w, q, k, v, do, args.steps)
-    out["cold_cache"] = {"ms_per_step": cold, "value": useful / (cold * 1e-3) / 1e12, "unit": "TFLOP/s (useful)",
-                         "note": "3 input/output sets cycled; `value` above re-uses one set (inputs partly cache-resident)"}
     if not args.no_extras:
+        out["measured_peaks"] = measured_peaks(torch, binding)
+        out["frac_measured_mfma_peak"] = value / out["measured_peaks"]["mfma_bf16_TFLOPs"]
+        cold = cold_cache_ms(torch, binding, w, q, k, v, do, args.steps)
+        out["cold_cache"] = {"ms_per_step": cold, "value": useful / (cold * 1e-3) / 1e12, "unit": "TFLOP/s (useful)",
+                             "note": "3 input/output sets cycled; `value` above re-uses one set (inputs partly cache-resident)"}
         nrun = no_posid_run(torch, binding, w, q, k, v, do)
         nms, _ = timed(torch, nrun, max(5, args.steps // 2), 3, with_events=False)
         del nrun
