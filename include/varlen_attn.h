@@ -42,7 +42,7 @@ typedef enum {
   VA_ERR_NULL = 1,        /* a required pointer is NULL                                    */
   VA_ERR_SHAPE = 2,       /* rows/tokens/heads/head_dim <= 0, N >= 2^31, Hq % Hkv != 0      */
   VA_ERR_UNSUPPORTED = 3, /* unknown dtype / id type / gradient type, head_dim > 256, Hq > 65535, or
-                             (MFMA path) (tokens_per_row + 256) * Hq * d * 2 >= 2^32         */
+                             (MFMA path) (tokens_per_row + 256) * Hq * d * 2 >= 2^32 - 256   */
   VA_ERR_WORKSPACE = 4,   /* plan buffer or workspace smaller than the *_bytes() query says */
   VA_ERR_HIP = 5          /* a launch failed (hipGetLastError after the launch)             */
 } va_status;

@@ -54,7 +54,7 @@ va_status check_common(const va_segments *seg, int32_t rows, int32_t T, int32_t 
   if (d > 256) return VA_ERR_UNSUPPORTED;
   if (hq > 65535) return VA_ERR_UNSUPPORTED;  // a grid dimension of the D kernel
   // the MFMA kernels address one packed row's K/V (or Q/dO) through 32-bit byte offsets
-  if (use_mfma(dt, d) && ((long long)T + 256) * hq * d * 2 >= (1ll << 32)) return VA_ERR_UNSUPPORTED;
+  if (use_mfma(dt, d) && ((long long)T + 256) * hq * d * 2 >= 0xffffff00ll) return VA_ERR_UNSUPPORTED;  // largest buffer size
   return VA_OK;
 }
 

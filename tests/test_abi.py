@@ -139,6 +139,19 @@ def test_attn_validation(L):
 
     assert bwd(*withb(6, None)) == 1
     assert bwd(*withb(9, 5)) == 3
+    # gradient type: fp32, or the inputs' own 16-bit type (bf16 also with fp32 inputs)
+    for dt, gdt, bad in ((binding.VA_BF16, binding.VA_F16, True), (binding.VA_F16, binding.VA_BF16, True),
+                         (binding.VA_F32, binding.VA_F16, True)):
+        a = withb(9, gdt)
+        a[16] = dt
+        assert (bwd(*a) == 3) == bad
+    # MFMA path: 32-bit byte offsets inside one packed row
+    big = with_(7, 1 << 20)                                # tokens_per_row 2^20 ...
+    big[8], big[9], big[10], big[11] = 64, 64, 128, binding.VA_BF16   # ... x 64 heads x 256 B >= 2^32
+    assert fwd(*big) == 3
+    big[8], big[9] = 8, 8                                  # 2^20 x 8 x 256 B = 2^31: fine for validation
+    big[5] = None
+    assert fwd(*big) == 1                                  # (rejected later, for the missing segments)
     assert bwd(*withb(18, None)) == 1                      # workspace required
     assert bwd(*withb(19, 16)) == 4                        # workspace too small
     assert L.va_attn_workspace_bytes(16, 2, 2, 16, 1) >= 16 * 2 * 4
