@@ -395,6 +395,124 @@ tile_order_fused_kernel(const int32_t *__restrict__ seg_start, const int32_t *__
   order_kv[rkv] = tile;
 }
 
+// ---- one launch for streams of up to kSingleMaxTokens tokens -----------------------------------
+// One workgroup of 1024 threads holds the whole stream: boundary scan without carries (8 consecutive
+// tokens per thread), then tile keys and ranks after a barrier.  All global traffic is coalesced
+// (thread i touches tokens i, i + 1024, ...): the ids' start flags go through LDS to the threads that
+// scan them, and seg_id / seg_start / seg_end come back through LDS to be written out the same way --
+// one compute unit cannot afford 64 cache lines per load or store instruction.  Used when the stream
+// fits, because at this size every extra launch costs as much as the work.
+constexpr int kSingleThreads = 1024;
+constexpr int kSingleMaxTokens = kSingleThreads * kPerThread;  // 8192
+constexpr int kSingleMaxTiles = 256;
+
+template <typename IdT>
+__global__ void __launch_bounds__(kSingleThreads)
+pack_single_kernel(const IdT *__restrict__ pos, int N, int T, int tiles_per_row, int ntiles,
+                   int32_t *__restrict__ cu, int32_t *__restrict__ seg_id, int32_t *__restrict__ seg_start,
+                   int32_t *__restrict__ seg_end, int32_t *__restrict__ meta, int32_t *__restrict__ order_q,
+                   int32_t *__restrict__ order_kv) {
+  constexpr int kWaves = kSingleThreads / 64;
+  __shared__ int s_cnt[kWaves], s_last[kWaves], s_first[kWaves];
+  __shared__ int32_t s_ss[kSingleMaxTokens], s_se[kSingleMaxTokens], s_id[kSingleMaxTokens];
+  __shared__ __attribute__((aligned(8))) uint8_t s_flag[kSingleMaxTokens];
+  __shared__ unsigned long long s_q[kSingleMaxTiles], s_kv[kSingleMaxTiles];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  {  // start flags, coalesced; all loads in flight together
+    IdT id[kPerThread];
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) id[e] = pos[min(e * kSingleThreads + (int)threadIdx.x, N - 1)];
+    int r = threadIdx.x % T;
+    const int step = kSingleThreads % T;
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) {
+      const int t = e * kSingleThreads + threadIdx.x;
+      s_flag[t] = t < N && (id[e] == 0 || r == 0);
+      r += step;
+      if (r >= T) r -= T;
+    }
+  }
+  __syncthreads();
+  const int base = threadIdx.x * kPerThread;
+  bool flag[kPerThread];
+  {
+    const unsigned long long f8 = *(const unsigned long long *)(s_flag + base);
+#pragma unroll
+    for (int e = 0; e < kPerThread; ++e) flag[e] = (f8 >> (8 * e)) & 1;
+  }
+  int cnt = 0, last = -1, first = N;
+#pragma unroll
+  for (int e = 0; e < kPerThread; ++e) {
+    const int t = base + e;
+    if (flag[e]) { ++cnt; last = t; first = min(first, t); }
+  }
+  const int icnt = wave_incl_add(cnt), ilast = wave_incl_max(last), sfirst = wave_suffix_min(first);
+  if (lane == 63) { s_cnt[w] = icnt; s_last[w] = ilast; }
+  if (lane == 0) s_first[w] = sfirst;
+  __syncthreads();
+  int ecnt = __shfl_up(icnt, 1, 64), elast = __shfl_up(ilast, 1, 64), efirst = __shfl_down(sfirst, 1, 64);
+  if (lane == 0) { ecnt = 0; elast = -1; }
+  if (lane == 63) efirst = N;
+  for (int i = 0; i < w; ++i) { ecnt += s_cnt[i]; elast = max(elast, s_last[i]); }
+  for (int i = w + 1; i < kWaves; ++i) efirst = min(efirst, s_first[i]);
+  int nxt[kPerThread];
+  int run = efirst;
+#pragma unroll
+  for (int e = kPerThread - 1; e >= 0; --e) {
+    nxt[e] = run;
+    if (flag[e]) run = base + e;
+  }
+  int c = ecnt, l = elast, longest = 0;
+#pragma unroll
+  for (int e = 0; e < kPerThread; ++e) {
+    const int t = base + e;
+    if (t >= N) break;
+    if (flag[e]) { cu[c] = t; ++c; l = t; longest = max(longest, nxt[e] - t); }
+    s_id[t] = c - 1;
+    s_ss[t] = l;
+    s_se[t] = nxt[e];
+  }
+  for (int o = 32; o > 0; o >>= 1) longest = max(longest, __shfl_xor(longest, o, 64));
+  __syncthreads();  // s_cnt free; s_id / s_ss / s_se complete
+  if (lane == 0) s_cnt[w] = longest;
+  if (threadIdx.x == (N - 1) / kPerThread) {  // the thread holding the last token knows the number of examples
+    meta[0] = c;
+    for (int i = 2; i < 8; ++i) meta[i] = 0;
+    cu[c] = N;
+  }
+#pragma unroll
+  for (int e = 0; e < kPerThread; ++e) {  // coalesced write-out
+    const int t = e * kSingleThreads + threadIdx.x;
+    if (t < N) { seg_id[t] = s_id[t]; seg_start[t] = s_ss[t]; seg_end[t] = s_se[t]; }
+  }
+  // tile keys
+  if ((int)threadIdx.x < ntiles) {
+    const int tile = threadIdx.x;
+    const int r = tile / tiles_per_row, m = tile % tiles_per_row;
+    const int t0 = r * T + m * kTile;
+    const int t1 = min(t0 + kTile, (r + 1) * T) - 1;
+    const int ss0 = s_ss[t0], se0 = s_se[t0], ss1 = s_ss[t1], se1 = s_se[t1];
+    s_q[tile] = tile_key(se0 - ss0, ss0, (t1 >> 6) - (ss0 >> 6) + 1);
+    s_kv[tile] = tile_key(se1 - ss1, ss1, ((se1 - 1) >> 6) - (t0 >> 6) + 1);
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int i = 1; i < kWaves; ++i) longest = max(longest, s_cnt[i]);
+    meta[1] = longest;
+  }
+  if ((int)threadIdx.x < ntiles) {
+    const int tile = threadIdx.x;
+    const unsigned long long cq = s_q[tile], ckv = s_kv[tile];
+    int rq = 0, rkv = 0;
+    for (int o = 0; o < ntiles; ++o) {
+      rq += (s_q[o] > cq) || (s_q[o] == cq && o < tile);
+      rkv += (s_kv[o] > ckv) || (s_kv[o] == ckv && o < tile);
+    }
+    order_q[rq] = tile;
+    order_kv[rkv] = tile;
+  }
+}
+
 }  // namespace
 
 hipError_t launch_pack(const void *pos, va_itype it, int rows, int T, const va_segments &seg,
@@ -402,6 +520,17 @@ hipError_t launch_pack(const void *pos, va_itype it, int rows, int T, const va_s
   const int N = rows * T;
   const int nchunks = ceil_div(N, kScanChunk);
   const int tiles_per_row = ceil_div(T, kTile), ntiles = rows * tiles_per_row;
+  if (N <= kSingleMaxTokens && ntiles <= kSingleMaxTiles) {
+    if (it == VA_I64)
+      pack_single_kernel<int64_t><<<1, kSingleThreads, 0, stream>>>(
+          (const int64_t *)pos, N, T, tiles_per_row, ntiles, seg.cu_seqlens, seg.seg_id, seg.seg_start, seg.seg_end,
+          seg.meta, seg.q_tile_order, seg.kv_tile_order);
+    else
+      pack_single_kernel<int32_t><<<1, kSingleThreads, 0, stream>>>(
+          (const int32_t *)pos, N, T, tiles_per_row, ntiles, seg.cu_seqlens, seg.seg_id, seg.seg_start, seg.seg_end,
+          seg.meta, seg.q_tile_order, seg.kv_tile_order);
+    return hipGetLastError();
+  }
   if (nchunks <= kOnePassMaxChunks && ntiles <= kFusedMaxTiles) {
     int32_t *chunk_longest = seg.scratch;  // [nchunks]
     if (it == VA_I64)
