@@ -377,7 +377,7 @@ tile_order_fused_kernel(const int32_t *__restrict__ seg_start, const int32_t *__
     s_q[tile] = tile_key(se0 - ss0, ss0, (t1 >> 6) - (ss0 >> 6) + 1);
     s_kv[tile] = tile_key(se1 - ss1, ss1, ((se1 - 1) >> 6) - (t0 >> 6) + 1);
   }
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
+  if (blockIdx.x == 0 && threadIdx.x == 0 && nchunks > 0) {  // nchunks == 0: max_seqlen is already in meta
     int longest = 0;
     for (int i = 0; i < nchunks; ++i) longest = max(longest, chunk_longest[i]);
     meta[1] = longest;
@@ -560,6 +560,11 @@ hipError_t launch_pack(const void *pos, va_itype it, int rows, int T, const va_s
     scan_finalize_kernel<int32_t><<<nchunks, kScanThreads, 0, stream>>>(
         (const int32_t *)pos, N, T, carry, seg.cu_seqlens, seg.seg_id, seg.seg_start, seg.seg_end, seg.meta);
   const int tb = ceil_div(ntiles, 256);
+  if (ntiles <= kFusedMaxTiles) {  // keys of all tiles fit in LDS: keys and ranks in one launch
+    tile_order_fused_kernel<<<tb, 256, 0, stream>>>(seg.seg_start, seg.seg_end, T, tiles_per_row, ntiles, nullptr, 0,
+                                                    seg.meta, seg.q_tile_order, seg.kv_tile_order);
+    return hipGetLastError();
+  }
   tile_cost_kernel<<<tb, 256, 0, stream>>>(seg.seg_start, seg.seg_end, T, tiles_per_row, ntiles, cost_q, cost_kv);
   tile_rank_kernel<<<tb, 256, 0, stream>>>(cost_q, cost_kv, ntiles, seg.q_tile_order, seg.kv_tile_order);
   return hipGetLastError();

@@ -66,6 +66,7 @@ def test_configs(cfg, dtype):
     (1, 4097, 5000, 5), (7, 1000, 1, 6), (2, 70001, 900, 7), (1, 300000, 2500, 8),
     (1, 8192, 8192, 9), (2, 4096, 700, 10), (1, 8193, 600, 11),   # around the one-launch limit (8192 tokens)
     (300, 20, 20, 12), (2000, 4, 3, 13),                          # <= 8192 tokens but more than 256 tiles
+    (3000, 5, 4, 14),                                             # more than 2048 tiles: separate key / rank kernels
 ])
 def test_ragged_shapes(R, T, maxlen, seed):
     rng = np.random.default_rng(seed)
