@@ -1,0 +1,65 @@
+"""Host-side parts of the benchmark's contract (no GPU): the one-GPU rule, the FLOP accounting, the
+profile summary it reads, and that nothing of the product path reaches into the oracle."""
+import ast
+import os
+import subprocess
+import sys
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+import bench  # noqa: E402
+from paper_2407_09105_amd import workloads as wl  # noqa: E402
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    p = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode != 0 and p.stdout.strip() == ""
+    assert "ONE GPU" in p.stderr and "--gpus 2" in p.stderr
+
+
+def test_flop_accounting_counts_unmasked_pairs():
+    # useful FLOPs: 4d forward + 10d backward per unmasked (i, j) pair and query head, pairs = sum L(L+1)/2
+    w = wl.make_workload(1, tensors=False)
+    assert w.stats["pairs"] == sum(L * (L + 1) // 2 for L in (3, 5, 1, 7))
+    f, b = bench.flops(w.cfg, w.stats["pairs"])
+    assert f == 4 * w.cfg.d * w.cfg.hq * w.stats["pairs"] and b == 10 * w.cfg.d * w.cfg.hq * w.stats["pairs"]
+    w2 = wl.make_workload(2, tensors=False)
+    assert w2.cfg.n_tokens == 8192 and sum(w2.lengths[0]) == 8192
+    assert w2.stats["pairs"] == sum(L * (L + 1) // 2 for L in w2.lengths[0])
+
+
+def test_traffic_summary_is_readable():
+    for kernel in ("fwd_mfma_kernel", "dq_mfma_kernel", "dkdv_mfma_kernel"):
+        t = bench.read_traffic(2, kernel)
+        assert t is not None and 2.0e8 < t < 2.0e9, kernel     # bytes per launch on config 2
+    assert bench.read_traffic(2, "no_such_kernel") is None
+
+
+def test_product_path_never_imports_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2407_09105_amd")
+    for name in os.listdir(pkg):
+        if not name.endswith(".py"):
+            continue
+        tree = ast.parse(open(os.path.join(pkg, name)).read())
+        for node in ast.walk(tree):
+            mods = []
+            if isinstance(node, ast.Import):
+                mods = [a.name for a in node.names]
+            elif isinstance(node, ast.ImportFrom):
+                mods = [node.module or ""]
+            assert not any(m == "oracle" or m.startswith("oracle.") for m in mods), name
+    for name in os.listdir(os.path.join(pkg, "csrc")):
+        text = open(os.path.join(pkg, "csrc", name)).read()
+        assert "oracle" not in text.lower(), name
+    # and the oracle imports nothing of the package
+    for name in os.listdir(os.path.join(ROOT, "oracle")):
+        if name.endswith((".py", ".c")):
+            assert "paper_2407_09105_amd" not in open(os.path.join(ROOT, "oracle", name)).read(), name
+
+
+def test_padded_layout_groups_of_four():
+    lay = wl.padded_layout([[3, 9, 4, 6, 2, 8]], group=4)
+    assert lay == [(3, 9), (9, 9), (4, 9), (6, 9), (2, 8), (8, 8)]
+    assert np.sum([p for _, p in lay]) == 52
