@@ -59,37 +59,30 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   const int t0 = r * T + m * VA_TILE + sub * kBT;
   if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
   const int t_last = min(t0 + kBT, row_end) - 1;
-  const int jb_lo = uniform(seg_start[t0]) / kBS, jb_hi = t_last / kBS;
-
+  // Everything the prologue needs depends on the tile only: all of it is requested before any of it
+  // is looked at (a value made wave-uniform right after its load would hold the next load back by
+  // a full memory round trip, several times in a row).
   const int iw0 = t0 + wave * 32;
   const int iw1 = min(iw0 + 31, t_last);
   const bool wave_ok = iw0 <= t_last;
   const bool wave_full = iw0 + 31 <= t_last;
-  const int ss_min = uniform(seg_start[min(iw0, t_last)]);
-  const int ss_max = uniform(seg_start[iw1 < iw0 ? t_last : iw1]);
   const int i_abs = iw0 + l32;
   const bool row_ok = i_abs <= t_last;
   const int i_ld = min(i_abs, t_last);  // clamped: loads stay in bounds, results of dead rows are dropped
-  const int ss_i = row_ok ? seg_start[i_ld] : 0x7fffffff;
-
+  const int ss_t0_v = seg_start[t0];
+  const int ss_min_v = seg_start[min(iw0, t_last)];
+  const int ss_max_v = seg_start[iw1 < iw0 ? t_last : iw1];
+  const int ss_i_v = seg_start[i_ld];
   x8 qf[kKs], gf[kKs];  // Q and dO rows of this lane: B operands
   load_row_fragments<E, kKs>(Q + ((size_t)i_ld * hq + h) * d, d, half, qf);
   load_row_fragments<E, kKs>(dO + ((size_t)i_ld * hq + h) * d, d, half, gf);
-  const float lse2 = LSE[(size_t)h * N + i_ld] * kLog2e;
-  // D = dO . O of this lane's query row, computed here (each lane of a pair holds half of the row)
-  // and left in `delta` for the dK/dV kernel, which runs after this one
-  float dl = 0.f;
-  {
-    x8 of[kKs];
-    load_row_fragments<E, kKs>(O + ((size_t)i_ld * hq + h) * d, d, half, of);
-#pragma unroll
-    for (int ks = 0; ks < kKs; ++ks)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) dl = fmaf((float)gf[ks][e], (float)of[ks][e], dl);
-    dl = pair_sum(dl);
-    if (row_ok && half == 0) delta[(size_t)h * N + i_abs] = dl;
-  }
+  x8 of[kKs];
+  load_row_fragments<E, kKs>(O + ((size_t)i_ld * hq + h) * d, d, half, of);
+  const float lse_v = LSE[(size_t)h * N + i_ld];
 
+  const int jb_lo = uniform(ss_t0_v) / kBS, jb_hi = t_last / kBS;
+  const int ss_min = uniform(ss_min_v), ss_max = uniform(ss_max_v);
+  const int ss_i = row_ok ? ss_i_v : 0x7fffffff;
   f32x16 acc[kCb];
 #pragma unroll
   for (int cb = 0; cb < kCb; ++cb)
@@ -123,6 +116,19 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
       __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, o, 0, 0, 0);
     }
   };
+  uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
+  copy_block(K0, V0, jb_lo);  // the first block is on its way while D is formed
+
+  const float lse2 = lse_v * kLog2e;
+  // D = dO . O of this lane's query row, computed here (each lane of a pair holds half of the row)
+  // and left in `delta` for the dK/dV kernel, which runs after this one
+  float dl = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < kKs; ++ks)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) dl = fmaf((float)gf[ks][e], (float)of[ks][e], dl);
+  dl = pair_sum(dl);
+  if (row_ok && half == 0) delta[(size_t)h * N + i_abs] = dl;
 
   // One iteration: start the copy of block jb+1 into the other stage (last read before the previous
   // barrier), consume block jb from (Kb, Vb); the barrier at the end publishes the copied block.
@@ -165,9 +171,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
     __syncthreads();
   };
 
-  uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
-  copy_block(K0, V0, jb_lo);
-  wait_all_loads();  // Q / dO fragments too: inside the loop only block copies are in flight
+  wait_all_loads();  // every prologue load has landed: inside the loop only block copies are in flight
   __syncthreads();
   for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
     iteration(jb, K0, V0, K1, V1);
@@ -210,6 +214,11 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   __shared__ __attribute__((aligned(16))) uint16_t stages[kStagesElems];
   // P hand-over: [key group 4][parity 2][part 2][lane 64] x 16 B
   __shared__ __attribute__((aligned(16))) u32x4 exch[4 * 2 * 2 * 64];
+  // the tile's own K rows and V rows (swizzled like the streamed blocks), only used in the prologue:
+  // each wave takes its 32-row operand from here.  Going through LDS lets the rows arrive as whole
+  // 1 KB transfers; loading the per-lane fragments straight from HBM (32 rows x 32 B per
+  // instruction) took 3 us per workgroup.
+  __shared__ __attribute__((aligned(16))) uint16_t kv_tile[2 * kBT * kD];
 
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int kg = wave & 3;
@@ -244,7 +253,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const float stat_mul = stat_is_lse ? -1.f / scale : -1.f;
   float rstat = 0.f;
   auto copy_block = [&](uint16_t *dst, int hh, int ib) {
-    if (threadIdx.x < 2 * kBS) {
+    {  // every thread loads (a load under a condition would be waited for at the end of the branch)
       const int i = min(ib * kBS + stat_row, N - 1);
       rstat = stat_src[(size_t)(g * G + hh) * N + i];
     }
@@ -262,23 +271,41 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   uint16_t *S0 = stages, *S1 = stages + kStage;
   copy_block(S0, 0, ib_lo);  // needs nothing but the tile: in flight while the bounds arrive
 
-  const int ib_hi = (uniform(seg_end[t_last]) - 1) / kBS;
-  const int nb = ib_hi - ib_lo + 1;
-  const int n_it = nb * G;
-
+  // Everything else the prologue needs depends on the tile only: all of it is requested before any
+  // of it is looked at (a value made wave-uniform right after its load would hold the next load
+  // back by a full memory round trip, four times in a row).
   const int jw0 = t0 + kg * 32;
   const int jw1 = min(jw0 + 31, t_last);
   const bool wave_ok = jw0 <= t_last;
   const bool wave_full = jw0 + 31 <= t_last;
-  const int se_min = uniform(seg_end[min(jw0, t_last)]);
-  const int se_max = uniform(seg_end[jw1 < jw0 ? t_last : jw1]);
   const int j_abs = jw0 + l32;
   const bool row_ok = j_abs <= t_last;
   const int j_ld = min(j_abs, t_last);
-  const int se_j = row_ok ? seg_end[j_ld] : 0;
+  const int se_last_v = seg_end[t_last];
+  const int se_min_v = seg_end[min(jw0, t_last)];
+  const int se_max_v = seg_end[jw1 < jw0 ? t_last : jw1];
+  const int se_j_v = seg_end[j_ld];
+  {  // K and V rows t0 .. t0 + 127 of head g -> kv_tile: 32 transfers of 4 rows per tensor, 4 per wave
+    const size_t kv_row_bytes = (size_t)hkv * d * 2;
+    const size_t kv_off = (size_t)t0 * kv_row_bytes, kv_total = (size_t)N * kv_row_bytes;
+    const buffer_t kb = make_buffer((const char *)K + kv_off, kv_total - kv_off);
+    const buffer_t vb = make_buffer((const char *)V + kv_off, kv_total - kv_off);
+    const uint32_t o0 = dma_lane_offset(lane, dma_row, kv_row_bytes, g, d);
+    const uint32_t step = (uint32_t)(32 * kv_row_bytes);
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const uint32_t o = dma_ok ? o0 + p * step : kPastEnd;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(kb, (lds_void)(kv_tile + (8 * p + wave) * 512), 16, o, 0, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(vb, (lds_void)(kv_tile + kBT * kD + (8 * p + wave) * 512), 16, o, 0, 0, 0);
+    }
+  }
 
-  x8 rf[kKs];  // this lane's key row: K (V side computes S) or V (K side computes dP)
-  load_row_fragments<E, kKs>((k_side ? V : K) + ((size_t)j_ld * hkv + g) * d, d, half, rf);
+  const int ib_hi = (uniform(se_last_v) - 1) / kBS;  // query blocks end with the example of the tile's last key
+  const int nb = ib_hi - ib_lo + 1;
+  const int n_it = nb * G;
+  const int se_min = uniform(se_min_v), se_max = uniform(se_max_v);
+  const int se_j = row_ok ? se_j_v : 0;  // queries j_abs <= i < se_j see key j_abs
+
   f32x16 acc[kCb];
 #pragma unroll
   for (int cb = 0; cb < kCb; ++cb)
@@ -290,6 +317,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   swz_tr_lane_off(lane, tr_lane);
   u32x4 *const ex = exch + kg * 256 + lane;  // + parity * 128 + part * 64
 
+  x8 rf[kKs];  // this lane's key row: K (the V side computes S) or V (the K side computes dP); set below
   int ib_cur = ib_lo, ib_nxt = ib_lo, hh_nxt = 0, par = 0;
   auto iteration = [&](int it, const uint16_t *__restrict__ cur, uint16_t *__restrict__ nxt) {
     const bool more = it + 1 < n_it;  // workgroup-uniform
@@ -362,6 +390,8 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   put_stats(S0);
   wait_all_loads();
   lds_barrier();
+#pragma unroll
+  for (int ks = 0; ks < kKs; ++ks) rf[ks] = swz_read_row<E>(kv_tile + (k_side ? kBT * kD : 0), row_lane, ks, kg * 32);
   for (int it = 0; it < n_it; it += 2) {  // bounds are workgroup-uniform: barriers stay aligned
     iteration(it, S0, S1);
     if (it + 1 < n_it) iteration(it + 1, S1, S0);

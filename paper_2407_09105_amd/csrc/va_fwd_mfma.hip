@@ -63,21 +63,25 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   const int t0 = r * T + m * VA_TILE + sub * kBM;
   if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
   const int t_last = min(t0 + kBM, row_end) - 1;
-  const int jb_lo = uniform(seg_start[t0]) / kBN, jb_hi = t_last / kBN;  // key blocks of this tile
-
-  // this wave's rows (wave-uniform) and this lane's query row
-  const int iw0 = t0 + wave * 32;
+  // Everything the prologue needs depends on the tile only: all of it is requested before any of it
+  // is looked at (a value made wave-uniform right after its load would hold the next load back by
+  // a full memory round trip, several times in a row).
+  const int iw0 = t0 + wave * 32;  // this wave's rows (wave-uniform) and this lane's query row
   const int iw1 = min(iw0 + 31, t_last);
   const bool wave_ok = iw0 <= t_last;
   const bool wave_full = iw0 + 31 <= t_last;
-  const int ss_min = uniform(seg_start[min(iw0, t_last)]);
-  const int ss_max = uniform(seg_start[iw1 < iw0 ? t_last : iw1]);
   const int i_abs = iw0 + l32;
   const bool row_ok = i_abs <= t_last;
   const int i_ld = min(i_abs, t_last);  // clamped: loads stay in bounds, results of dead rows are dropped
-  const int ss_i = row_ok ? seg_start[i_ld] : 0x7fffffff;
-
-  x8 qf[kKs];  // B operands of S^T = K Q^T; k-steps of 16 (loaded below, behind the first block copy)
+  const int ss_t0_v = seg_start[t0];
+  const int ss_min_v = seg_start[min(iw0, t_last)];
+  const int ss_max_v = seg_start[iw1 < iw0 ? t_last : iw1];
+  const int ss_i_v = seg_start[i_ld];
+  x8 qf[kKs];  // B operands of S^T = K Q^T; k-steps of 16
+  load_row_fragments<E, kKs>(Q + ((size_t)i_ld * hq + h) * d, d, half, qf);
+  const int jb_lo = uniform(ss_t0_v) / kBN, jb_hi = t_last / kBN;  // key blocks of this tile
+  const int ss_min = uniform(ss_min_v), ss_max = uniform(ss_max_v);
+  const int ss_i = row_ok ? ss_i_v : 0x7fffffff;
 
   f32x16 o_acc[kCb];
 #pragma unroll
@@ -176,8 +180,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   };
 
   uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
-  copy_block(K0, V0, jb_lo);  // in flight while the Q fragments are fetched
-  load_row_fragments<E, kKs>(Q + ((size_t)i_ld * hq + h) * d, d, half, qf);
+  copy_block(K0, V0, jb_lo);
   wait_all_loads();  // Q fragments too: inside the loop only block copies are in flight
   __syncthreads();
   for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
