@@ -59,9 +59,12 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   const int t0 = r * T + m * VA_TILE + sub * kBT;
   if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
   const int t_last = min(t0 + kBT, row_end) - 1;
-  // Everything the prologue needs depends on the tile only: all of it is requested before any of it
-  // is looked at (a value made wave-uniform right after its load would hold the next load back by
-  // a full memory round trip, several times in a row).
+  // Prologue.  The tile's own Q, dO and O rows come in through LDS as whole-row block copies, into
+  // the memory of the K/V stages, which is idle until the loop starts (loading the per-lane
+  // fragments straight from HBM -- 32 rows x 32 B per instruction -- took 8 us per workgroup):
+  //   round 1: Q -> first half of the stage memory, dO -> second half; scalars (example bounds, LSE)
+  //   round 2: O -> second half, first K/V block -> first half (= stage 0 of the loop)
+  // All loads of a round are requested before any is consumed.
   const int iw0 = t0 + wave * 32;
   const int iw1 = min(iw0 + 31, t_last);
   const bool wave_ok = iw0 <= t_last;
@@ -69,15 +72,32 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   const int i_abs = iw0 + l32;
   const bool row_ok = i_abs <= t_last;
   const int i_ld = min(i_abs, t_last);  // clamped: loads stay in bounds, results of dead rows are dropped
+  const uint32_t row_lane = swz_row_lane_off(lane);
+  uint32_t tr_lane[2];
+  swz_tr_lane_off(lane, tr_lane);
+  typedef __attribute__((address_space(3))) void *lds_void;
+  uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
+  const int dma_row = wave * 4 + (lane >> 4);
+  const bool dma_ok = dma_lane_ok(lane, dma_row, d);  // the same for every transfer of this lane (rows 16 apart)
+
+  const size_t q_row_bytes = (size_t)hq * d * 2;
+  const size_t q_off = (size_t)t0 * q_row_bytes, q_total = (size_t)N * q_row_bytes;
+  const uint32_t tile_off = dma_lane_offset(lane, dma_row, q_row_bytes, h, d);
+  // 128 rows of one tensor (head h) -> 32 KB at dst: 8 transfers of 4 rows per wave
+  auto copy_tile = [&](const uint16_t *X, uint16_t *dst) {
+    const buffer_t xb = make_buffer((const char *)X + q_off, q_total - q_off);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+      const uint32_t o = dma_ok ? tile_off + p * (uint32_t)(16 * q_row_bytes) : kPastEnd;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (lds_void)(dst + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+    }
+  };
+  copy_tile(Q, K0);
+  copy_tile(dO, K1);
   const int ss_t0_v = seg_start[t0];
   const int ss_min_v = seg_start[min(iw0, t_last)];
   const int ss_max_v = seg_start[iw1 < iw0 ? t_last : iw1];
   const int ss_i_v = seg_start[i_ld];
-  x8 qf[kKs], gf[kKs];  // Q and dO rows of this lane: B operands
-  load_row_fragments<E, kKs>(Q + ((size_t)i_ld * hq + h) * d, d, half, qf);
-  load_row_fragments<E, kKs>(dO + ((size_t)i_ld * hq + h) * d, d, half, gf);
-  x8 of[kKs];
-  load_row_fragments<E, kKs>(O + ((size_t)i_ld * hq + h) * d, d, half, of);
   const float lse_v = LSE[(size_t)h * N + i_ld];
 
   const int jb_lo = uniform(ss_t0_v) / kBS, jb_hi = t_last / kBS;
@@ -89,10 +109,6 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[cb][v] = 0.f;
 
-  const uint32_t row_lane = swz_row_lane_off(lane);
-  uint32_t tr_lane[2];
-  swz_tr_lane_off(lane, tr_lane);
-
   const size_t row_bytes = (size_t)hkv * d * 2;
   const size_t base_off = (size_t)jb_lo * kBS * row_bytes;
   const size_t total = (size_t)N * row_bytes;
@@ -101,12 +117,9 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   // HBM -> LDS copy of a 64-row block by the load unit (see the forward kernel): 4 loads per wave and
   // tensor, each 1 KB = 4 rows at LDS address (4 p + wave) KB; lane L lands at row 16 p + 4 wave + L / 16,
   // chunk position L % 16, and fetches global chunk (L % 16) ^ swz(row).
-  const int dma_row = wave * 4 + (lane >> 4);
   const uint32_t dma_off = dma_lane_offset(lane, dma_row, row_bytes, g, d);
-  const bool dma_ok = dma_lane_ok(lane, dma_row, d);  // the same for all four transfers (rows 16 apart)
   const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
   const uint32_t p_bytes = (uint32_t)(16 * row_bytes);
-  typedef __attribute__((address_space(3))) void *lds_void;
   auto copy_block = [&](uint16_t *Kd, uint16_t *Vd, int jb) {  // rows past the tensor arrive as zeros
     const uint32_t off = dma_off + (uint32_t)(jb - jb_lo) * blk_bytes;
 #pragma unroll
@@ -116,19 +129,33 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
       __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, o, 0, 0, 0);
     }
   };
-  uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
-  copy_block(K0, V0, jb_lo);  // the first block is on its way while D is formed
 
+  x8 qf[kKs], gf[kKs];  // Q and dO rows of this lane: B operands
+  wait_all_loads();
+  __syncthreads();  // round 1 has landed
+#pragma unroll
+  for (int ks = 0; ks < kKs; ++ks) {
+    qf[ks] = swz_read_row<E>(K0, row_lane, ks, wave * 32);
+    gf[ks] = swz_read_row<E>(K1, row_lane, ks, wave * 32);
+  }
+  __syncthreads();  // every wave has its Q and dO fragments: the memory is free again
+  copy_tile(O, K1);
+  copy_block(K0, V0, jb_lo);
   const float lse2 = lse_v * kLog2e;
+  wait_all_loads();
+  __syncthreads();  // round 2 has landed
   // D = dO . O of this lane's query row, computed here (each lane of a pair holds half of the row)
   // and left in `delta` for the dK/dV kernel, which runs after this one
   float dl = 0.f;
 #pragma unroll
-  for (int ks = 0; ks < kKs; ++ks)
+  for (int ks = 0; ks < kKs; ++ks) {
+    const x8 of = swz_read_row<E>(K1, row_lane, ks, wave * 32);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) dl = fmaf((float)gf[ks][e], (float)of[ks][e], dl);
+    for (int e = 0; e < 8; ++e) dl = fmaf((float)gf[ks][e], (float)of[e], dl);
+  }
   dl = pair_sum(dl);
   if (row_ok && half == 0) delta[(size_t)h * N + i_abs] = dl;
+  __syncthreads();  // O has been read: stage 1 may receive the second K/V block
 
   // One iteration: start the copy of block jb+1 into the other stage (last read before the previous
   // barrier), consume block jb from (Kb, Vb); the barrier at the end publishes the copied block.
@@ -171,8 +198,6 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
     __syncthreads();
   };
 
-  wait_all_loads();  // every prologue load has landed: inside the loop only block copies are in flight
-  __syncthreads();
   for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
     iteration(jb, K0, V0, K1, V1);
     if (jb + 1 <= jb_hi) iteration(jb + 1, K1, V1, K0, V0);
