@@ -60,6 +60,13 @@ va_status check_common(const va_segments *seg, int32_t rows, int32_t T, int32_t 
 
 }  // namespace
 
+#ifdef VA_TRACE
+namespace va {
+hipError_t trace_read_fwd(void *host, size_t bytes);
+hipError_t trace_read_bwd(int which, void *host, size_t bytes);
+}
+#endif
+
 extern "C" {
 
 size_t va_plan_bytes(int32_t rows, int32_t tokens_per_row) {
@@ -220,5 +227,15 @@ const char *va_status_string(va_status s) {
 }
 
 const char *va_version(void) { return "varlen_attn 0.1 (gfx950)"; }
+
+#ifdef VA_TRACE
+// Timeline build only (-DVA_TRACE): copies the per-workgroup records of the last launch of the
+// forward (0), dQ (1) or dK/dV (2) kernel to the host; synchronises the device.
+int va_trace_read(int kernel, void *host, size_t bytes) {
+  if (hipDeviceSynchronize() != hipSuccess) return VA_ERR_HIP;
+  const hipError_t e = kernel == 0 ? va::trace_read_fwd(host, bytes) : va::trace_read_bwd(kernel - 1, host, bytes);
+  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
+}
+#endif
 
 }  // extern "C"

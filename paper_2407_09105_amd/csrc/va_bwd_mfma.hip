@@ -26,6 +26,8 @@ constexpr int kSub = VA_TILE / kBT;  // workgroup tiles per schedule tile
 constexpr int kBS = 64;              // streamed rows per LDS block
 constexpr int kBlk = kBS * kD;       // elements of one swizzled [64][128] LDS block (16 KB)
 constexpr float kLog2e = 1.4426950408889634f;
+VA_TRACE_DECL(g_trace_dq);
+VA_TRACE_DECL(g_trace_dkdv);
 
 
 // ---------------------------------------------------------------------------------------------
@@ -45,6 +47,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   // two stages of {K block, V block}, swizzled
   __shared__ __attribute__((aligned(16))) uint16_t lds[4 * kBlk];
   static_assert(4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit");
+  VA_TRACE_T(tr0);
 
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int l32 = lane & 31, half = lane >> 5;
@@ -156,6 +159,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   dl = pair_sum(dl);
   if (row_ok && half == 0) delta[(size_t)h * N + i_abs] = dl;
   __syncthreads();  // O has been read: stage 1 may receive the second K/V block
+  VA_TRACE_T(tr1);
 
   // One iteration: start the copy of block jb+1 into the other stage (last read before the previous
   // barrier), consume block jb from (Kb, Vb); the barrier at the end publishes the copied block.
@@ -203,17 +207,19 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
     if (jb + 1 <= jb_hi) iteration(jb + 1, K1, V1, K0, V0);
   }
 
+  VA_TRACE_T(tr2);
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
   store_transposed_tile<EOut, kCb>(acc, scale, stage, dQ, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h, d);
+  VA_TRACE_STORE(g_trace_dq, tr0, tr1, tr2, jb_hi - jb_lo + 1);
 }
 
 // ---------------------------------------------------------------------------------------------
 // dK/dV with the two gradients on different waves.  Workgroup = 8 waves = (128-key tile, KV head);
 // waves 0..3 ("V side") and 4..7 ("K side") each own 32 keys, wave w and w + 4 the same ones, and
 // share a SIMD.  Per 32-query sub-block:
-//   V side: S = Q K^T (on -LSE / scale), P = exp2, mask; hands P (bf16) to its partner through LDS;
+//   V side: S = Q K^T (on -LSE / scale), P = exp2, mask; leaves P (bf16) in LDS for its partner;
 //           dV^T += dO^T P.
-//   K side: dP = dO V^T (on -D); after the hand-over dS = P * dP; dK^T += Q^T dS.
+//   K side: dP = dO V^T (on -D); one sub-block later, with that P: dS = P * dP; dK^T += Q^T dS.
 // Each wave holds one accumulator tile and one operand tile (about 200 registers), so two waves fit
 // per SIMD and one wave's exp / convert / LDS work overlaps the other's matrix instructions.
 constexpr int kDkdvThreads = 512;
@@ -244,6 +250,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   // 1 KB transfers; loading the per-lane fragments straight from HBM (32 rows x 32 B per
   // instruction) took 3 us per workgroup.
   __shared__ __attribute__((aligned(16))) uint16_t kv_tile[2 * kBT * kD];
+  VA_TRACE_T(tr0);
 
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int kg = wave & 3;
@@ -343,91 +350,137 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   u32x4 *const ex = exch + kg * 256 + lane;  // + parity * 128 + part * 64
 
   x8 rf[kKs];  // this lane's key row: K (the V side computes S) or V (the K side computes dP); set below
-  int ib_cur = ib_lo, ib_nxt = ib_lo, hh_nxt = 0, par = 0;
-  auto iteration = [&](int it, const uint16_t *__restrict__ cur, uint16_t *__restrict__ nxt) {
-    const bool more = it + 1 < n_it;  // workgroup-uniform
+  int ib_cur = ib_lo, ib_nxt = ib_lo, hh_nxt = 0;
+  // The K side runs one sub-block behind the V side: in step k the V side computes S(k), P(k) (left in
+  // LDS) and dV(k), the K side computes dP(k) and, with the P(k-1) published by the previous barrier,
+  // dS(k-1) and dK(k-1).  No wave waits for another inside a step; one barrier ends each step.  The
+  // two sides run separate loops (same barriers, same block copies) so that each keeps only its own
+  // values in registers.
+  auto read_ty = [&](x8 (&ty)[2][kCb], const uint16_t *__restrict__ Ys, int row0) {
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int cb = 0; cb < kCb; ++cb) ty[s2][cb] = swz_read_tr<E>(Ys, tr_lane, cb, row0 + s2 * 16);
+  };
+  auto first_product = [&](f32x16 &x, const uint16_t *__restrict__ Xs, const float *__restrict__ st, int row0) {
+#pragma unroll
+    for (int q4 = 0; q4 < 4; ++q4) {
+      const f32x4 c = *(const f32x4 *)(st + row0 + q4 * 8 + half * 4);
+#pragma unroll
+      for (int b = 0; b < 4; ++b) x[q4 * 4 + b] = c[b];
+    }
+    x8 ax[kKs];
+#pragma unroll
+    for (int ks = 0; ks < kKs; ++ks) ax[ks] = swz_read_row<E>(Xs, row_lane, ks, row0);
+#pragma unroll
+    for (int ks = 0; ks < kKs; ++ks) x = mfma32(ax[ks], rf[ks], x);  // S - LSE / scale, or dP - D
+  };
+  auto second_product = [&](const f32x16 &x, const x8 (&ty)[2][kCb]) {
+    const x8 f0 = pack_x8<E>(x, 0), f1 = pack_x8<E>(x, 8);
+#pragma unroll
+    for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(ty[0][cb], f0, acc[cb]);  // dV^T += dO^T P, dK^T += Q^T dS
+#pragma unroll
+    for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(ty[1][cb], f1, acc[cb]);
+  };
+  auto v_step = [&](const uint16_t *__restrict__ cur, int il, int row0, int pw) {
+    f32x16 x;
+    x8 ty[2][kCb];
+    first_product(x, cur, (const float *)(cur + 2 * kBlk), row0);
+    read_ty(ty, cur + kBlk, row0);
+#pragma unroll
+    for (int v = 0; v < 16; ++v) x[v] = __builtin_amdgcn_exp2f(x[v] * scale_log2);  // P
+    const bool interior = wave_full && il >= jw1 && il + 31 < se_min;
+    if (!interior) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = il + acc_row(v, half);
+        if (i < j_abs || i >= se_j) x[v] = 0.f;
+      }
+    }
+    ex[pw * 128] = __builtin_bit_cast(u32x4, pack_x8<E>(x, 0));
+    ex[pw * 128 + 64] = __builtin_bit_cast(u32x4, pack_x8<E>(x, 8));
+    second_product(x, ty);
+  };
+  auto k_finish = [&](f32x16 &x, const x8 (&ty)[2][kCb], int pr) {  // dS = P (dP - D); dK
+    const x8 p0 = as_x8<E>(ex[pr * 128]), p1 = as_x8<E>(ex[pr * 128 + 64]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { x[e] *= (float)p0[e]; x[8 + e] *= (float)p1[e]; }
+    second_product(x, ty);
+  };
+  bool more = false;
+  auto begin_block = [&](int it, uint16_t *__restrict__ nxt) {  // returns the block's first query
+    more = it + 1 < n_it;  // workgroup-uniform
     if (++ib_nxt > ib_hi) { ib_nxt = ib_lo; ++hh_nxt; }
     if (more) copy_block(nxt, hh_nxt, ib_nxt);
-    const uint16_t *Xs = cur + (k_side ? kBlk : 0);   // rows of S's / dP's left operand: Q or dO
-    const uint16_t *Ys = cur + (k_side ? 0 : kBlk);   // transposed operand of the second product: Q^T or dO^T
-    const float *st = (const float *)(cur + 2 * kBlk) + (k_side ? kBS : 0);  // -LSE / scale or -D
     const int i0 = ib_cur * kBS;
     ib_cur = ib_nxt;
-#pragma unroll 1
-    for (int sb = 0; sb < 2; ++sb) {
-      const int il = i0 + sb * 32, row0 = sb * 32;
-      const bool active = wave_ok && il + 31 >= jw0 && il < se_max;  // wave-uniform, same for both sides
-      f32x16 x;
-      x8 ty[2][kCb];
-      if (active) {
-#pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-          const f32x4 c = *(const f32x4 *)(st + row0 + q4 * 8 + half * 4);
-#pragma unroll
-          for (int b = 0; b < 4; ++b) x[q4 * 4 + b] = c[b];
-        }
-        x8 ax[kKs];
-#pragma unroll
-        for (int ks = 0; ks < kKs; ++ks) ax[ks] = swz_read_row<E>(Xs, row_lane, ks, row0);
-#pragma unroll
-        for (int ks = 0; ks < kKs; ++ks) x = mfma32(ax[ks], rf[ks], x);  // S - LSE / scale, or dP - D
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-          for (int cb = 0; cb < kCb; ++cb) ty[s2][cb] = swz_read_tr<E>(Ys, tr_lane, cb, row0 + s2 * 16);
-        if (!k_side) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v) x[v] = __builtin_amdgcn_exp2f(x[v] * scale_log2);  // P
-          const bool interior = wave_full && il >= jw1 && il + 31 < se_min;
-          if (!interior) {
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-              const int i = il + acc_row(v, half);
-              if (i < j_abs || i >= se_j) x[v] = 0.f;
-            }
-          }
-          ex[par * 128] = __builtin_bit_cast(u32x4, pack_x8<E>(x, 0));
-          ex[par * 128 + 64] = __builtin_bit_cast(u32x4, pack_x8<E>(x, 8));
-        }
-      }
-      lds_barrier();  // P of this sub-block is in LDS
-      if (active) {
-        x8 f0, f1;
-        if (k_side) {
-          const x8 p0 = as_x8<E>(ex[par * 128]), p1 = as_x8<E>(ex[par * 128 + 64]);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) { x[e] *= (float)p0[e]; x[8 + e] *= (float)p1[e]; }  // dS
-        }
-        f0 = pack_x8<E>(x, 0);
-        f1 = pack_x8<E>(x, 8);
-#pragma unroll
-        for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(ty[0][cb], f0, acc[cb]);  // dV^T += dO^T P, dK^T += Q^T dS
-#pragma unroll
-        for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(ty[1][cb], f1, acc[cb]);
-      }
-      par ^= 1;
-    }
+    return i0;
+  };
+  auto end_block = [&](uint16_t *__restrict__ nxt) {
     if (more) put_stats(nxt);
     wait_all_loads();
-    lds_barrier();  // next block published; every read of this stage is done
+    lds_barrier();  // P published; next block published; every read of this stage is done
   };
-
+  // wave-uniform and the same on both sides: does sub-block [il, il + 32) hold a pair of this wave?
+  auto is_active = [&](int il) { return wave_ok && il + 31 >= jw0 && il < se_max; };
+  auto v_iteration = [&](int it, const uint16_t *__restrict__ cur, uint16_t *__restrict__ nxt) {
+    const int i0 = begin_block(it, nxt);
+    if (is_active(i0)) v_step(cur, i0, 0, 0);
+    lds_barrier();
+    if (is_active(i0 + 32)) v_step(cur, i0 + 32, 32, 1);
+    end_block(nxt);
+  };
+  f32x16 xa, xb;       // K side: dP - D of the two sub-blocks of a block, each waiting for its P
+  x8 tyb[2][kCb];      // K side: Q^T fragments of sub-block b (its stage is overwritten before they are used)
+  bool act_b = false;  // K side: sub-block b of the previous block is waiting for its P
+  auto k_iteration = [&](int it, const uint16_t *__restrict__ cur, uint16_t *__restrict__ nxt) {
+    const int i0 = begin_block(it, nxt);
+    const float *st = (const float *)(cur + 2 * kBlk) + kBS;
+    const bool act0 = is_active(i0), act1 = is_active(i0 + 32);
+    // step 2 it: dP of sub-block a; dS, dK of the previous block's b (P at parity 1)
+    if (act0) first_product(xa, cur + kBlk, st, 0);
+    if (act_b) k_finish(xb, tyb, 1);
+    lds_barrier();
+    // step 2 it + 1: dP of sub-block b; dS, dK of a (P at parity 0)
+    if (act1) {
+      first_product(xb, cur + kBlk, st, 32);
+      read_ty(tyb, cur, 32);
+    }
+    if (act0) {
+      x8 tya[2][kCb];
+      read_ty(tya, cur, 0);
+      k_finish(xa, tya, 0);
+    }
+    act_b = act1;
+    end_block(nxt);
+  };
   put_stats(S0);
   wait_all_loads();
   lds_barrier();
 #pragma unroll
   for (int ks = 0; ks < kKs; ++ks) rf[ks] = swz_read_row<E>(kv_tile + (k_side ? kBT * kD : 0), row_lane, ks, kg * 32);
-  for (int it = 0; it < n_it; it += 2) {  // bounds are workgroup-uniform: barriers stay aligned
-    iteration(it, S0, S1);
-    if (it + 1 < n_it) iteration(it + 1, S1, S0);
+  VA_TRACE_T(tr1);
+  if (!k_side) {
+    for (int it = 0; it < n_it; it += 2) {  // bounds are workgroup-uniform: barriers stay aligned
+      v_iteration(it, S0, S1);
+      if (it + 1 < n_it) v_iteration(it + 1, S1, S0);
+    }
+  } else {
+    for (int it = 0; it < n_it; it += 2) {
+      k_iteration(it, S0, S1);
+      if (it + 1 < n_it) k_iteration(it + 1, S1, S0);
+    }
+    if (act_b) k_finish(xb, tyb, 1);  // the last sub-block's dK
   }
 
+  VA_TRACE_T(tr2);
   float *stage = (float *)stages + wave * kStageFloatsPerWave;
   const int nrows = wave_ok ? jw1 - jw0 + 1 : 0;
   if (k_side)
     store_transposed_tile<EOut, kCb>(acc, scale, stage, dK, jw0, nrows, hkv, g, d);
   else
     store_transposed_tile<EOut, kCb>(acc, 1.f, stage, dV, jw0, nrows, hkv, g, d);
+  VA_TRACE_STORE(g_trace_dkdv, tr0, tr1, tr2, n_it);
 }
 
 }  // namespace
@@ -483,5 +536,13 @@ hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const v
   }
   return hipGetLastError();
 }
+
+#ifdef VA_TRACE
+hipError_t trace_read_bwd(int which, void *host, size_t bytes) {
+  if (bytes > sizeof(g_trace_dq)) bytes = sizeof(g_trace_dq);
+  return which == 0 ? hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_dq), bytes)
+                    : hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_dkdv), bytes);
+}
+#endif
 
 }  // namespace va

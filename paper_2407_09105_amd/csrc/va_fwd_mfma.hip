@@ -32,6 +32,7 @@ constexpr int kBN = 32;           // key rows per LDS block
 constexpr int kBlk = kBN * kD;    // elements of one swizzled [32][128] LDS block (8 KB)
 constexpr int kLdsElems = (4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4) ? 4 * kBlk : 4 * kStageFloatsPerWave * 2;
 constexpr float kLazyLog2 = 8.f;  // keep a stale row maximum while probabilities stay <= 2^8
+VA_TRACE_DECL(g_trace_fwd);
 
 // E: element type (Bf16 / F16); kDh: head_dim rounded up to 64, 96 or 128 (k-steps and column blocks
 // the kernel is unrolled for); d: the tensors' head_dim (a multiple of 8, <= kDh).
@@ -46,6 +47,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   // stage 0 = {K, V} at lds[0 .. 2 kBlk), stage 1 = {K, V} at lds[2 kBlk .. 4 kBlk)
   __shared__ __attribute__((aligned(16))) uint16_t lds[kLdsElems];
 
+  VA_TRACE_T(tr0);
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int l32 = lane & 31, half = lane >> 5;
   const uint32_t row_lane = swz_row_lane_off(lane);
@@ -183,17 +185,20 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   copy_block(K0, V0, jb_lo);
   wait_all_loads();  // Q fragments too: inside the loop only block copies are in flight
   __syncthreads();
+  VA_TRACE_T(tr1);
   for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
     iteration(jb, K0, V0, K1, V1);
     if (jb + 1 <= jb_hi) iteration(jb + 1, K1, V1, K0, V0);
   }
 
   // ---- epilogue: normalise, stage O through LDS, coalesced stores ----
+  VA_TRACE_T(tr2);
   const float l_tot = pair_sum(l_run);
   const float inv = row_ok ? 1.f / l_tot : 0.f;
   if (row_ok && half == 0) LSE[(size_t)h * N + i_abs] = m_ref * scale + __logf(l_tot);
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
   store_transposed_tile<E, kCb>(o_acc, inv, stage, O, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h, d);
+  VA_TRACE_STORE(g_trace_fwd, tr0, tr1, tr2, jb_hi - jb_lo + 1);
 }
 
 }  // namespace
@@ -226,5 +231,11 @@ hipError_t launch_mfma_fwd(const void *Q, const void *K, const void *V, void *O,
     launch_fwd_e<Bf16>(Q, K, V, O, LSE, seg, rows, T, hq, hkv, d, scale, (unsigned)nwg, stream);
   return hipGetLastError();
 }
+
+#ifdef VA_TRACE
+hipError_t trace_read_fwd(void *host, size_t bytes) {
+  return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_fwd), bytes < sizeof(g_trace_fwd) ? bytes : sizeof(g_trace_fwd));
+}
+#endif
 
 }  // namespace va
