@@ -202,8 +202,30 @@ def measured_peaks(torch, binding):
     e1.record()
     torch.cuda.synchronize()
     copy = 5 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    # the matrix instructions with realistic operands and in the company they keep in the kernels
+    ops = torch.randn(32768, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    clocks = torch.zeros(2, dtype=torch.int64, device="cuda")
+    mixes = {}
+    for name, lds, valu in (("mfma_only", 0, 0), ("lds16", 16, 0), ("lds8", 8, 0),
+                            ("lds16_valu24_fwd_mix", 16, 24), ("lds16_valu12", 16, 12), ("lds8_valu16", 8, 16)):
+        for _ in range(12):   # long enough for the clock governor to settle
+            fl = binding.probe_mix(ops, lds, valu, sink, clocks, 6000)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(8):
+            binding.probe_mix(ops, lds, valu, sink, clocks, 6000)
+        e1.record()
+        torch.cuda.synchronize()
+        c = clocks.cpu().numpy()
+        mixes[name] = {"TFLOPs": 8 * fl / (e0.elapsed_time(e1) * 1e-3) / 1e12,
+                       "shader_clock_MHz": float(c[0]) / max(float(c[1]), 1.0) * 100.0}
     return {"mfma_bf16_TFLOPs": mfma, "device_copy_GBs": copy,
-            "note": "bf16 32x32x16 matrix instructions only, 2 waves per SIMD; 256 MiB device-to-device copy (read + write bytes)"}
+            "mfma_bf16_mix_TFLOPs": mixes,
+            "note": "mfma_bf16_TFLOPs: bf16 32x32x16 matrix instructions only, constant small operands, 2 waves per SIMD; "
+                    "mfma_bf16_mix_TFLOPs: the same with N(0,1) bf16 operands plus, per 16 matrix instructions, "
+                    "ldsN = N 1 KB fragment reads from LDS and valuM = M groups of {fma, exp2, max, add}, all independent "
+                    "(what the power limit and the issue slots leave to the matrix pipe; shader clock read in-kernel); "
+                    "device_copy_GBs: 256 MiB device-to-device copy (read + write bytes)"}
 
 
 def cold_cache_ms(torch, binding, w, q, k, v, do, steps, copies=3):

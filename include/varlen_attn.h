@@ -202,6 +202,23 @@ va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K
  */
 va_status va_probe_mfma(float *sink, int32_t iters, double *flops /* host, out */, void *stream);
 
+/*
+ * Measurement aid (no part of the method): the same matrix instructions in the company they keep
+ * in the attention kernels.  operands: device, 64 KB of 16-bit values with the bit patterns of real
+ * inputs (e.g. N(0,1) rounded to bf16), which the kernel stages in LDS and multiplies (the rate a
+ * power-limited GPU sustains depends on how many operand bits toggle).  Per 16 matrix instructions
+ * a wave also issues `lds_reads` 1 KB fragment reads from LDS and `valu_groups` groups of
+ * {fma, exp2, max, add}, all independent of the matrix instructions, 2 waves per SIMD.  Supported
+ * (lds_reads, valu_groups): (0,0), (8,0), (16,0), (16,24) - the forward kernel's mix -, (16,12) and
+ * (8,16); others return VA_ERR_UNSUPPORTED.  flops / time (caller's events on `stream`) bounds what
+ * a kernel with that instruction mix can reach on this GPU.  clocks (device, 2 x uint64, may be NULL)
+ * receives the shader-clock ticks and the 100 MHz wall-clock ticks of one wave's loop: their ratio
+ * is the clock the GPU held under that load.  sink: device, >= 64 floats, normally left untouched.
+ */
+va_status va_probe_mix(const void *operands, int32_t lds_reads, int32_t valu_groups, float *sink,
+                       uint64_t *clocks /* device, out */, int32_t iters, double *flops /* host, out */,
+                       void *stream);
+
 /* Static string for a status code. */
 const char *va_status_string(va_status s);
 

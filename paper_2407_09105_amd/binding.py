@@ -25,7 +25,7 @@ STAGE_D, STAGE_DKDV, STAGE_DQ = 1, 2, 4
 EXPORTS = (
     "va_plan_bytes", "va_segments_bind", "va_pack_to_cu_seqlens", "va_attn_workspace_bytes",
     "va_varlen_attn_fwd", "va_varlen_attn_bwd", "va_varlen_attn_bwd_stages", "va_collate_padding_free",
-    "va_rope_apply", "va_probe_mfma", "va_status_string", "va_version",
+    "va_rope_apply", "va_probe_mfma", "va_probe_mix", "va_status_string", "va_version",
 )
 
 
@@ -72,6 +72,9 @@ def lib() -> C.CDLL:
                                 C.c_int32, C.c_float, C.c_int, C.c_void_p]
     L.va_probe_mfma.restype = C.c_int
     L.va_probe_mfma.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
+    L.va_probe_mix.restype = C.c_int
+    L.va_probe_mix.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                               C.POINTER(C.c_double), C.c_void_p]
     L.va_status_string.restype = C.c_char_p
     L.va_status_string.argtypes = [C.c_int]
     L.va_version.restype = C.c_char_p
@@ -238,6 +241,24 @@ def probe_mfma(sink: torch.Tensor, iters: int) -> float:
         raise ValueError("sink must hold at least 64 float32")
     fl = C.c_double(0.0)
     _check("va_probe_mfma", lib().va_probe_mfma(sink.data_ptr(), int(iters), C.byref(fl), _stream()))
+    return fl.value
+
+
+def probe_mix(operands: torch.Tensor, lds_reads: int, valu_groups: int, sink: torch.Tensor,
+              clocks: Optional[torch.Tensor], iters: int) -> float:
+    """Enqueue the matrix + LDS + vector-ALU mix kernel; returns its matrix FLOPs (time it with events).
+    operands: >= 64 KB of 16-bit values on the device; clocks: 2 x int64 on the device or None."""
+    _need_cuda(operands, sink)
+    if operands.numel() * operands.element_size() < 65536:
+        raise ValueError("operands must hold at least 64 KB")
+    if sink.dtype != torch.float32 or sink.numel() < 64:
+        raise ValueError("sink must hold at least 64 float32")
+    if clocks is not None and (clocks.dtype != torch.int64 or clocks.numel() < 2 or not clocks.is_cuda):
+        raise ValueError("clocks must hold 2 int64 on the device")
+    fl = C.c_double(0.0)
+    _check("va_probe_mix", lib().va_probe_mix(operands.data_ptr(), int(lds_reads), int(valu_groups), sink.data_ptr(),
+                                              clocks.data_ptr() if clocks is not None else None, int(iters),
+                                              C.byref(fl), _stream()))
     return fl.value
 
 

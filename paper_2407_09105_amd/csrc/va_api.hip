@@ -142,6 +142,19 @@ va_status va_probe_mfma(float *sink, int32_t iters, double *flops, void *stream)
   return e == hipSuccess ? VA_OK : VA_ERR_HIP;
 }
 
+va_status va_probe_mix(const void *operands, int32_t lds_reads, int32_t valu_groups, float *sink,
+                       uint64_t *clocks, int32_t iters, double *flops, void *stream) {
+  if (!operands || !sink) return VA_ERR_NULL;
+  if (iters <= 0 || iters > (1 << 24)) return VA_ERR_SHAPE;
+  const bool known = (valu_groups == 0 && (lds_reads == 0 || lds_reads == 8 || lds_reads == 16)) ||
+                     (lds_reads == 16 && (valu_groups == 24 || valu_groups == 12)) ||
+                     (lds_reads == 8 && valu_groups == 16);
+  if (!known) return VA_ERR_UNSUPPORTED;
+  hipError_t e = va::launch_mix_probe(operands, lds_reads, valu_groups, sink, (unsigned long long *)clocks, iters,
+                                      flops, (hipStream_t)stream);
+  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
+}
+
 size_t va_attn_workspace_bytes(int32_t n_tokens, int32_t hq, int32_t hkv, int32_t d, int is_bwd) {
   if (n_tokens <= 0 || hq <= 0 || hkv <= 0 || d <= 0) return 0;
   if (!is_bwd) return 0;

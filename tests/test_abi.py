@@ -159,6 +159,18 @@ def test_attn_validation(L):
     assert L.va_attn_workspace_bytes(0, 2, 2, 16, 1) == 0
 
 
+def test_probe_validation(L):
+    """The measurement aids reject what they cannot run before launching anything."""
+    p = C.c_void_p(0x1000)
+    assert L.va_probe_mfma(None, 10, None, None) == 1
+    assert L.va_probe_mfma(p, 0, None, None) == 2
+    assert L.va_probe_mix(None, 16, 24, p, None, 10, None, None) == 1
+    assert L.va_probe_mix(p, 16, 24, None, None, 10, None, None) == 1
+    assert L.va_probe_mix(p, 16, 24, p, None, 0, None, None) == 2
+    assert L.va_probe_mix(p, 5, 24, p, None, 10, None, None) == 3      # not an instantiated mix
+    assert L.va_probe_mix(p, 8, 24, p, None, 10, None, None) == 3
+
+
 def test_strings(L):
     assert L.va_status_string(0) == b"ok"
     assert all(L.va_status_string(i) for i in range(7))
