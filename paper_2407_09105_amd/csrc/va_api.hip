@@ -33,12 +33,15 @@ bool plan_layout(int32_t rows, int32_t T, PlanLayout *L) {
   return true;
 }
 
-bool use_mfma(va_dtype dt, int d) {
+// The MFMA kernels take bf16 / fp16 tensors whose head_dim is a multiple of 8: the forward up to
+// 256, the backward up to kMfmaBwdMaxD; everything else runs on the plain kernels.
+constexpr int kMfmaFwdMaxD = 256, kMfmaBwdMaxD = 128;
+bool use_mfma(va_dtype dt, int d, int max_d) {
   static const bool force_generic = [] {
     const char *e = std::getenv("VA_FORCE_GENERIC");
     return e && e[0] == '1';
   }();
-  return (dt == VA_BF16 || dt == VA_F16) && d <= 128 && d % 8 == 0 && !force_generic;
+  return (dt == VA_BF16 || dt == VA_F16) && d <= max_d && d % 8 == 0 && !force_generic;
 }
 
 va_status check_common(const va_segments *seg, int32_t rows, int32_t T, int32_t hq, int32_t hkv,
@@ -54,7 +57,7 @@ va_status check_common(const va_segments *seg, int32_t rows, int32_t T, int32_t 
   if (d > 256) return VA_ERR_UNSUPPORTED;
   if (hq > 65535) return VA_ERR_UNSUPPORTED;  // a grid dimension of the D kernel
   // the MFMA kernels address one packed row's K/V (or Q/dO) through 32-bit byte offsets
-  if (use_mfma(dt, d) && ((long long)T + 256) * hq * d * 2 >= 0xffffff00ll) return VA_ERR_UNSUPPORTED;  // largest buffer size
+  if (use_mfma(dt, d, kMfmaFwdMaxD) && ((long long)T + 256) * hq * d * 2 >= 0xffffff00ll) return VA_ERR_UNSUPPORTED;  // largest buffer size
   return VA_OK;
 }
 
@@ -173,7 +176,7 @@ va_status va_varlen_attn_fwd(const void *Q, const void *K, const void *V, void *
   const int N = rows * tokens_per_row;
   const float scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)d);
   hipError_t e;
-  if (use_mfma(dt, d))
+  if (use_mfma(dt, d, kMfmaFwdMaxD))
     e = va::launch_mfma_fwd(Q, K, V, O, LSE, *seg, rows, tokens_per_row, hq, hkv, d, dt, scale, (hipStream_t)stream);
   else
     e = va::launch_generic_fwd(Q, K, V, O, LSE, *seg, N, hq, hkv, d, dt, scale, (hipStream_t)stream);
@@ -201,7 +204,7 @@ va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K
   float *delta = (float *)workspace;
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = hipSuccess;
-  const bool mfma = use_mfma(dt, d);
+  const bool mfma = use_mfma(dt, d, kMfmaBwdMaxD);
   // the MFMA dQ kernel forms D itself (and stores it for the dK/dV kernel, which it precedes)
   if ((stages & VA_STAGE_D) && !(mfma && (stages & VA_STAGE_DQ))) e = va::launch_delta(dO, O, delta, N, hq, d, dt, st);
   if (e != hipSuccess) return VA_ERR_HIP;

@@ -1,4 +1,4 @@
-// Forward kernel: causal attention inside each example of a packed stream, bf16 / fp16, head_dim <= 128.
+// Forward kernel: causal attention inside each example of a packed stream, bf16 / fp16, head_dim <= 256.
 //
 // What it computes (see include/varlen_attn.h): O_i = softmax_j(scale q_i.k_j) v_j over the keys
 // a <= j <= i of token i's own example, and LSE_i.  The example bound a = seg_start[i] comes from
@@ -30,22 +30,26 @@ constexpr int kBM = 128;          // query rows per workgroup
 constexpr int kSub = VA_TILE / kBM;
 constexpr int kBN = 32;           // key rows per LDS block
 constexpr int kBlk = kBN * kD;    // elements of one swizzled [32][128] LDS block (8 KB)
-constexpr int kLdsElems = (4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4) ? 4 * kBlk : 4 * kStageFloatsPerWave * 2;
+constexpr int kStagingElems = 4 * kStageFloatsPerWave * 2;  // the result staging of four waves, in 16-bit units
 constexpr float kLazyLog2 = 8.f;  // keep a stale row maximum while probabilities stay <= 2^8
 VA_TRACE_DECL(g_trace_fwd);
 
-// E: element type (Bf16 / F16); kDh: head_dim rounded up to 64, 96 or 128 (k-steps and column blocks
-// the kernel is unrolled for); d: the tensors' head_dim (a multiple of 8, <= kDh).
+// E: element type (Bf16 / F16); kDh: head_dim rounded up to 64, 96, 128 or 256 (k-steps and column
+// blocks the kernel is unrolled for); d: the tensors' head_dim (a multiple of 8, <= kDh).  With
+// kDh = 256 a block of K or V is two swizzled [32][128] sub-blocks (columns 0..127 and 128..255),
+// the stages are twice as large and two workgroups share a CU instead of three.
 template <class E, int kDh>
-__global__ void __launch_bounds__(256, 3)
+__global__ void __launch_bounds__(256, kDh > 128 ? 2 : 3)
 fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
                 const uint16_t *__restrict__ V, uint16_t *__restrict__ O, float *__restrict__ LSE,
                 const int32_t *__restrict__ seg_start, const int32_t *__restrict__ q_tile_order,
                 int N, int T, int tiles_per_row, int hq, int hkv, int d, float scale_log2, float scale) {
   constexpr int kKs = kDh / 16, kCb = kDh / 32;
+  constexpr int kHf = kDh > 128 ? 2 : 1;  // 128-column sub-blocks per block
+  constexpr int kBlkT = kBlk * kHf;       // elements of one tensor's block
   typedef typename E::x8 x8;
-  // stage 0 = {K, V} at lds[0 .. 2 kBlk), stage 1 = {K, V} at lds[2 kBlk .. 4 kBlk)
-  __shared__ __attribute__((aligned(16))) uint16_t lds[kLdsElems];
+  // stage 0 = {K, V} at lds[0 .. 2 kBlkT), stage 1 = {K, V} at lds[2 kBlkT .. 4 kBlkT)
+  __shared__ __attribute__((aligned(16))) uint16_t lds[4 * kBlkT > kStagingElems ? 4 * kBlkT : kStagingElems];
 
   VA_TRACE_T(tr0);
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
@@ -104,18 +108,22 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   // chunk position L % 16, and therefore fetches global chunk (L % 16) ^ swz(row) of that row.
   const int dma_row = wave * 4 + (lane >> 4);
   const uint32_t dma_off = dma_lane_offset(lane, dma_row, row_bytes, g, d);
-  const bool dma_ok = dma_lane_ok(lane, dma_row, d);  // same for every transfer of this lane (rows 16 apart)
+  bool dma_ok[kHf];  // the same for every transfer of this lane into a sub-block (rows 16 apart)
+#pragma unroll
+  for (int hf = 0; hf < kHf; ++hf) dma_ok[hf] = dma_lane_ok(lane, dma_row, d - 128 * hf);
   const uint32_t blk_bytes = (uint32_t)(kBN * row_bytes);
   const uint32_t p_bytes = (uint32_t)(16 * row_bytes);
   typedef __attribute__((address_space(3))) void *lds_void;
   auto copy_block = [&](uint16_t *Kd, uint16_t *Vd, int jb) {  // rows past the tensor arrive as zeros
     const uint32_t off = dma_off + (uint32_t)(jb - jb_lo) * blk_bytes;
 #pragma unroll
-    for (int p = 0; p < kBN / 16; ++p) {
-      const uint32_t o = dma_ok ? off + p * p_bytes : kPastEnd;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + (4 * p + wave) * 512), 16, o, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, o, 0, 0, 0);
-    }
+    for (int hf = 0; hf < kHf; ++hf)
+#pragma unroll
+      for (int p = 0; p < kBN / 16; ++p) {
+        const uint32_t o = dma_ok[hf] ? off + p * p_bytes + hf * 256 : kPastEnd;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + hf * kBlk + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + hf * kBlk + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+      }
   };
 
   // One iteration: start the copy of block jb+1 into the other stage (last read before the previous
@@ -134,7 +142,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < kKs; ++ks) s = mfma32(swz_read_row<E>(Kb, row_lane, ks, sb * 32), qf[ks], s);
+        for (int ks = 0; ks < kKs; ++ks) s = mfma32(swz_read_row<E>(Kb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32), qf[ks], s);
         const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
         if (!interior) {
 #pragma unroll
@@ -174,14 +182,14 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
           const x8 pf = pack_x8<E>(s, 8 * s2);
 #pragma unroll
           for (int cb = 0; cb < kCb; ++cb)
-            o_acc[cb] = mfma32(swz_read_tr<E>(Vb, tr_lane, cb, sb * 32 + s2 * 16), pf, o_acc[cb]);
+            o_acc[cb] = mfma32(swz_read_tr<E>(Vb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + s2 * 16), pf, o_acc[cb]);
         }
       }
     }
     __syncthreads();
   };
 
-  uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
+  uint16_t *K0 = lds, *V0 = lds + kBlkT, *K1 = lds + 2 * kBlkT, *V1 = lds + 3 * kBlkT;
   copy_block(K0, V0, jb_lo);
   wait_all_loads();  // Q fragments too: inside the loop only block copies are in flight
   __syncthreads();
@@ -215,7 +223,8 @@ static void launch_fwd_e(const void *Q, const void *K, const void *V, void *O, f
                                                   hkv, d, scale_log2, scale)
   if (d <= 64) VA_LAUNCH_FWD(64);
   else if (d <= 96) VA_LAUNCH_FWD(96);
-  else VA_LAUNCH_FWD(128);
+  else if (d <= 128) VA_LAUNCH_FWD(128);
+  else VA_LAUNCH_FWD(256);
 #undef VA_LAUNCH_FWD
 }
 

@@ -38,10 +38,24 @@ def test_fp32_explicit_scale():
     _parity(wl.make_custom([[9, 3, 20]], 2, 2, 32, "f32", seed=6), scale=0.21)
 
 
-@pytest.mark.parametrize("d,dtype", [(20, "bf16"), (256, "bf16"), (36, "f16"), (256, "f16")])
+@pytest.mark.parametrize("d,dtype", [(20, "bf16"), (256, "bf16"), (36, "f16"), (256, "f16"), (250, "bf16")])
 def test_generic_16bit_other_head_dims(d, dtype):
-    # head dims the MFMA kernels do not take (not a multiple of 8, or above 128): plain kernels
+    # head dims that are not a multiple of 8 run on the plain kernels throughout
     _parity(wl.make_custom([[40, 7, 81]], 4, 2, d, dtype, seed=7), grad_dtype=torch.float32)
+
+
+# head_dim 256 (the gemma-style models of the paper's list) and the multiples of 8 between 128 and
+# 256: blocks are two 128-column halves, the upper one partly (or wholly) zero columns
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("d", [256, 136, 160, 192, 248])
+def test_mfma_head_dims_above_128(d, dtype):
+    w = wl.make_custom([[300, 45, 1, 1, 200, 93]], 4, 2, d, dtype, seed=40 + d)
+    _parity(w, grad_dtype=torch.float32)
+
+
+def test_mfma_head_dim_256_ragged_rows_and_16bit_grads():
+    w = wl.make_custom([[100, 219], [319], [1] * 319], 2, 1, 256, "bf16", seed=51)
+    _parity(w, grad_dtype=torch.bfloat16)
 
 
 MFMA_CASES = [
