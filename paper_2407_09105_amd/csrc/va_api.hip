@@ -34,8 +34,8 @@ bool plan_layout(int32_t rows, int32_t T, PlanLayout *L) {
 }
 
 // The MFMA kernels take bf16 / fp16 tensors whose head_dim is a multiple of 8: the forward up to
-// 256, the backward up to kMfmaBwdMaxD; everything else runs on the plain kernels.
-constexpr int kMfmaFwdMaxD = 256, kMfmaBwdMaxD = 128;
+// 256, the backward kernels up to kMfmaDqMaxD / kMfmaDkdvMaxD; everything else runs on the plain kernels.
+constexpr int kMfmaFwdMaxD = 256, kMfmaDqMaxD = 256, kMfmaDkdvMaxD = 128;
 bool use_mfma(va_dtype dt, int d, int max_d) {
   static const bool force_generic = [] {
     const char *e = std::getenv("VA_FORCE_GENERIC");
@@ -204,18 +204,19 @@ va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K
   float *delta = (float *)workspace;
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = hipSuccess;
-  const bool mfma = use_mfma(dt, d, kMfmaBwdMaxD);
+  const unsigned mfma_stages = ((use_mfma(dt, d, kMfmaDqMaxD) ? VA_STAGE_DQ : 0u) |
+                                (use_mfma(dt, d, kMfmaDkdvMaxD) ? VA_STAGE_DKDV : 0u)) & stages;
+  const unsigned plain_stages = stages & (VA_STAGE_DKDV | VA_STAGE_DQ) & ~mfma_stages;
   // the MFMA dQ kernel forms D itself (and stores it for the dK/dV kernel, which it precedes)
-  if ((stages & VA_STAGE_D) && !(mfma && (stages & VA_STAGE_DQ))) e = va::launch_delta(dO, O, delta, N, hq, d, dt, st);
+  if ((stages & VA_STAGE_D) && !(mfma_stages & VA_STAGE_DQ)) e = va::launch_delta(dO, O, delta, N, hq, d, dt, st);
   if (e != hipSuccess) return VA_ERR_HIP;
-  if (stages & (VA_STAGE_DKDV | VA_STAGE_DQ)) {
-    if (mfma)
-      e = va::launch_mfma_bwd(dO, Q, K, V, O, LSE, delta, dQ, dK, dV, grad_dt, *seg, rows, tokens_per_row, hq,
-                              hkv, d, dt, scale, st, stages);
-    else
-      e = va::launch_generic_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, N, hq, hkv, d, dt, scale,
-                                 st, stages);
-  }
+  if (mfma_stages)
+    e = va::launch_mfma_bwd(dO, Q, K, V, O, LSE, delta, dQ, dK, dV, grad_dt, *seg, rows, tokens_per_row, hq, hkv,
+                            d, dt, scale, st, mfma_stages);
+  if (e != hipSuccess) return VA_ERR_HIP;
+  if (plain_stages)
+    e = va::launch_generic_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, N, hq, hkv, d, dt, scale, st,
+                               plain_stages);
   return e == hipSuccess ? VA_OK : VA_ERR_HIP;
 }
 

@@ -35,7 +35,7 @@ VA_TRACE_DECL(g_trace_dkdv);
 // gradients' type (float, or E); kDh head_dim rounded up to 64, 96 or 128 (the unrolling); the
 // argument d is the tensors' head_dim (a multiple of 8, <= kDh).
 template <class E, class EOut, int kDh>
-__global__ void __launch_bounds__(256, 2)
+__global__ void __launch_bounds__(256, kDh > 128 ? 1 : 2)
 dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
                const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
                const uint16_t *__restrict__ O, const float *__restrict__ LSE,
@@ -43,9 +43,12 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
                const int32_t *__restrict__ seg_start, const int32_t *__restrict__ q_tile_order, int N,
                int T, int tiles_per_row, int hq, int hkv, int d, float scale_log2, float scale) {
   constexpr int kKs = kDh / 16, kCb = kDh / 32;
+  constexpr int kHf = kDh > 128 ? 2 : 1;   // 128-column sub-blocks per block (head_dim above 128: two)
+  constexpr int kBlkT = kBlk * kHf;        // elements of one tensor's streamed block
+  constexpr int kTileSub = kBT * kD;       // elements of one sub-block of the tile's own rows
   typedef typename E::x8 x8;
   // two stages of {K block, V block}, swizzled
-  __shared__ __attribute__((aligned(16))) uint16_t lds[4 * kBlk];
+  __shared__ __attribute__((aligned(16))) uint16_t lds[4 * kBlkT];
   static_assert(4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit");
   VA_TRACE_T(tr0);
 
@@ -79,21 +82,25 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   uint32_t tr_lane[2];
   swz_tr_lane_off(lane, tr_lane);
   typedef __attribute__((address_space(3))) void *lds_void;
-  uint16_t *K0 = lds, *V0 = lds + kBlk, *K1 = lds + 2 * kBlk, *V1 = lds + 3 * kBlk;
+  uint16_t *K0 = lds, *V0 = lds + kBlkT, *K1 = lds + 2 * kBlkT, *V1 = lds + 3 * kBlkT;
   const int dma_row = wave * 4 + (lane >> 4);
-  const bool dma_ok = dma_lane_ok(lane, dma_row, d);  // the same for every transfer of this lane (rows 16 apart)
+  bool dma_ok[kHf];  // the same for every transfer of this lane into a sub-block (rows 16 apart)
+#pragma unroll
+  for (int hf = 0; hf < kHf; ++hf) dma_ok[hf] = dma_lane_ok(lane, dma_row, d - 128 * hf);
 
   const size_t q_row_bytes = (size_t)hq * d * 2;
   const size_t q_off = (size_t)t0 * q_row_bytes, q_total = (size_t)N * q_row_bytes;
   const uint32_t tile_off = dma_lane_offset(lane, dma_row, q_row_bytes, h, d);
-  // 128 rows of one tensor (head h) -> 32 KB at dst: 8 transfers of 4 rows per wave
+  // 128 rows of one tensor (head h) -> 32 KB per sub-block at dst: 8 transfers of 4 rows per wave
   auto copy_tile = [&](const uint16_t *X, uint16_t *dst) {
     const buffer_t xb = make_buffer((const char *)X + q_off, q_total - q_off);
 #pragma unroll
-    for (int p = 0; p < 8; ++p) {
-      const uint32_t o = dma_ok ? tile_off + p * (uint32_t)(16 * q_row_bytes) : kPastEnd;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (lds_void)(dst + (4 * p + wave) * 512), 16, o, 0, 0, 0);
-    }
+    for (int hf = 0; hf < kHf; ++hf)
+#pragma unroll
+      for (int p = 0; p < 8; ++p) {
+        const uint32_t o = dma_ok[hf] ? tile_off + p * (uint32_t)(16 * q_row_bytes) + hf * 256 : kPastEnd;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (lds_void)(dst + hf * kTileSub + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+      }
   };
   copy_tile(Q, K0);
   copy_tile(dO, K1);
@@ -126,11 +133,13 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   auto copy_block = [&](uint16_t *Kd, uint16_t *Vd, int jb) {  // rows past the tensor arrive as zeros
     const uint32_t off = dma_off + (uint32_t)(jb - jb_lo) * blk_bytes;
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const uint32_t o = dma_ok ? off + p * p_bytes : kPastEnd;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + (4 * p + wave) * 512), 16, o, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + (4 * p + wave) * 512), 16, o, 0, 0, 0);
-    }
+    for (int hf = 0; hf < kHf; ++hf)
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const uint32_t o = dma_ok[hf] ? off + p * p_bytes + hf * 256 : kPastEnd;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + hf * kBlk + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + hf * kBlk + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+      }
   };
 
   x8 qf[kKs], gf[kKs];  // Q and dO rows of this lane: B operands
@@ -138,8 +147,8 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   __syncthreads();  // round 1 has landed
 #pragma unroll
   for (int ks = 0; ks < kKs; ++ks) {
-    qf[ks] = swz_read_row<E>(K0, row_lane, ks, wave * 32);
-    gf[ks] = swz_read_row<E>(K1, row_lane, ks, wave * 32);
+    qf[ks] = swz_read_row<E>(K0 + (ks >> 3) * kTileSub, row_lane, ks & 7, wave * 32);
+    gf[ks] = swz_read_row<E>(K1 + (ks >> 3) * kTileSub, row_lane, ks & 7, wave * 32);
   }
   __syncthreads();  // every wave has its Q and dO fragments: the memory is free again
   copy_tile(O, K1);
@@ -152,7 +161,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   float dl = 0.f;
 #pragma unroll
   for (int ks = 0; ks < kKs; ++ks) {
-    const x8 of = swz_read_row<E>(K1, row_lane, ks, wave * 32);
+    const x8 of = swz_read_row<E>(K1 + (ks >> 3) * kTileSub, row_lane, ks & 7, wave * 32);
 #pragma unroll
     for (int e = 0; e < 8; ++e) dl = fmaf((float)gf[ks][e], (float)of[e], dl);
   }
@@ -177,8 +186,8 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
         for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = -dl; }
 #pragma unroll
         for (int ks = 0; ks < kKs; ++ks) {
-          s = mfma32(swz_read_row<E>(Kb, row_lane, ks, sb * 32), qf[ks], s);     // S^T  = K Q^T
-          dp = mfma32(swz_read_row<E>(Vb, row_lane, ks, sb * 32), gf[ks], dp);   // dP^T - D = V dO^T - D
+          s = mfma32(swz_read_row<E>(Kb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32), qf[ks], s);     // S^T  = K Q^T
+          dp = mfma32(swz_read_row<E>(Vb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32), gf[ks], dp);   // dP^T - D = V dO^T - D
         }
         const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
 #pragma unroll
@@ -195,7 +204,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
           const x8 df = pack_x8<E>(s, 8 * s2);
 #pragma unroll
           for (int cb = 0; cb < kCb; ++cb)  // dQ^T += K^T dS^T
-            acc[cb] = mfma32(swz_read_tr<E>(Kb, tr_lane, cb, sb * 32 + s2 * 16), df, acc[cb]);
+            acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + s2 * 16), df, acc[cb]);
         }
       }
     }
@@ -495,17 +504,20 @@ static void launch_bwd_t(const uint16_t *g, const uint16_t *q, const uint16_t *k
     dq_mfma_kernel<E, EOut, kDh><<<gq, 256, 0, stream>>>(g, q, k, v, o, LSE, delta, dQ, seg.seg_start,
                                                          seg.q_tile_order, N, T, tiles_per_row, hq, hkv, d,
                                                          scale_log2, scale);
-  if (stages & VA_STAGE_DKDV)
-    dkdv_mfma_kernel<E, EOut, kDh><<<gkv, kDkdvThreads, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
-                                                                     seg.kv_tile_order, N, T, tiles_per_row, hq,
-                                                                     hkv, d, scale_log2, scale);
+  if constexpr (kDh <= 128) {
+    if (stages & VA_STAGE_DKDV)
+      dkdv_mfma_kernel<E, EOut, kDh><<<gkv, kDkdvThreads, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
+                                                                       seg.kv_tile_order, N, T, tiles_per_row, hq,
+                                                                       hkv, d, scale_log2, scale);
+  }
 }
 
 template <class E, class EOut, class... A>
 static void launch_bwd_d(int d, A... a) {
   if (d <= 64) launch_bwd_t<E, EOut, 64>(a...);
   else if (d <= 96) launch_bwd_t<E, EOut, 96>(a...);
-  else launch_bwd_t<E, EOut, 128>(a...);
+  else if (d <= 128) launch_bwd_t<E, EOut, 128>(a...);
+  else launch_bwd_t<E, EOut, 256>(a...);
 }
 
 hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const void *V, const void *O,
