@@ -35,7 +35,7 @@ bool plan_layout(int32_t rows, int32_t T, PlanLayout *L) {
 
 // The MFMA kernels take bf16 / fp16 tensors whose head_dim is a multiple of 8: the forward up to
 // 256, the backward kernels up to kMfmaDqMaxD / kMfmaDkdvMaxD; everything else runs on the plain kernels.
-constexpr int kMfmaFwdMaxD = 256, kMfmaDqMaxD = 256, kMfmaDkdvMaxD = 128;
+constexpr int kMfmaFwdMaxD = 256, kMfmaDqMaxD = 256, kMfmaDkdvMaxD = 256;
 bool use_mfma(va_dtype dt, int d, int max_d) {
   static const bool force_generic = [] {
     const char *e = std::getenv("VA_FORCE_GENERIC");

@@ -231,14 +231,23 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 //   K side: dP = dO V^T (on -D); one sub-block later, with that P: dS = P * dP; dK^T += Q^T dS.
 // Each wave holds one accumulator tile and one operand tile (about 200 registers), so two waves fit
 // per SIMD and one wave's exp / convert / LDS work overlaps the other's matrix instructions.
-constexpr int kDkdvThreads = 512;
+// head_dim above 128 (kDh = 256): operand and accumulator tiles are twice as large, so a workgroup is
+// 4 waves = (64-key tile, KV head), one wave per SIMD with 512 registers each; blocks are two
+// 128-column halves, and the tile's own K and V rows pass through the memory of the second stage.
+template <int kDh> struct DkdvShape {
+  static constexpr int kKg = kDh > 128 ? 2 : 4;         // key groups (of 32 keys) per workgroup
+  static constexpr int kWaves = 2 * kKg;                // V side + K side
+  static constexpr int kThreads = 64 * kWaves;
+  static constexpr int kKeys = 32 * kKg;                // keys per workgroup
+  static constexpr int kSubTiles = VA_TILE / kKeys;     // workgroup tiles per schedule tile
+};
 
 __device__ __forceinline__ void lds_barrier() {  // LDS traffic of this wave done, then workgroup barrier
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
 template <class E, class EOut, int kDh>
-__global__ void __launch_bounds__(kDkdvThreads, 1)
+__global__ void __launch_bounds__(DkdvShape<kDh>::kThreads, 1)
 dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
                   const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
                   const float *__restrict__ LSE, const float *__restrict__ delta, void *__restrict__ dK,
@@ -246,34 +255,42 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
                   const int32_t *__restrict__ kv_tile_order, int N, int T, int tiles_per_row, int hq,
                   int hkv, int d, float scale_log2, float scale) {
   constexpr int kKs = kDh / 16, kCb = kDh / 32;
+  constexpr int kHf = kDh > 128 ? 2 : 1;  // 128-column sub-blocks per block
+  constexpr int kBlkT = kBlk * kHf;       // elements of one tensor's streamed block
+  typedef DkdvShape<kDh> Shape;
+  constexpr int kKg = Shape::kKg, kWaves = Shape::kWaves, kKeys = Shape::kKeys, kSubTiles = Shape::kSubTiles;
+  constexpr int kKvSub = kKeys * kD;      // elements of one sub-block of the tile's own K (or V) rows
+  constexpr bool kKvInStage = kHf > 1;    // no room for a kv_tile of its own: the rows pass through stage 1
   typedef typename E::x8 x8;
   // two stages of {Q block, dO block (swizzled), -LSE / scale [64], -D [64]}; reused as the staging
-  // area of the result stores (8 waves)
-  constexpr int kStage = 2 * kBlk + 4 * kBS;
-  constexpr int kStagesElems = 8 * kStageFloatsPerWave * 2 > 2 * kStage ? 8 * kStageFloatsPerWave * 2 : 2 * kStage;
+  // area of the result stores
+  constexpr int kStage = 2 * kBlkT + 4 * kBS;
+  constexpr int kStagingElems = kWaves * kStageFloatsPerWave * 2;
+  constexpr int kStagesElems = kStagingElems > 2 * kStage ? kStagingElems : 2 * kStage;
+  static_assert(!kKvInStage || 2 * kHf * kKvSub <= kStage, "the tile's K and V rows must fit in one stage");
   __shared__ __attribute__((aligned(16))) uint16_t stages[kStagesElems];
-  // P hand-over: [key group 4][parity 2][part 2][lane 64] x 16 B
-  __shared__ __attribute__((aligned(16))) u32x4 exch[4 * 2 * 2 * 64];
+  // P hand-over: [key group][parity 2][part 2][lane 64] x 16 B
+  __shared__ __attribute__((aligned(16))) u32x4 exch[kKg * 2 * 2 * 64];
   // the tile's own K rows and V rows (swizzled like the streamed blocks), only used in the prologue:
   // each wave takes its 32-row operand from here.  Going through LDS lets the rows arrive as whole
   // 1 KB transfers; loading the per-lane fragments straight from HBM (32 rows x 32 B per
   // instruction) took 3 us per workgroup.
-  __shared__ __attribute__((aligned(16))) uint16_t kv_tile[2 * kBT * kD];
+  __shared__ __attribute__((aligned(16))) uint16_t kv_own[kKvInStage ? 8 : 2 * kKvSub];
   VA_TRACE_T(tr0);
 
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
-  const int kg = wave & 3;
-  const bool k_side = wave >= 4;
+  const int kg = wave % kKg;
+  const bool k_side = wave >= kKg;
   const int l32 = lane & 31, half = lane >> 5;
-  const int tile = uniform(kv_tile_order[blockIdx.x / (hkv * kSub)]);
-  const int sub = (blockIdx.x / hkv) % kSub;
+  const int tile = uniform(kv_tile_order[blockIdx.x / (hkv * kSubTiles)]);
+  const int sub = (blockIdx.x / hkv) % kSubTiles;
   const int g = blockIdx.x % hkv;
   const int G = hq / hkv;
   const int r = tile / tiles_per_row, m = tile % tiles_per_row;
   const int row_end = (r + 1) * T;
-  const int t0 = r * T + m * VA_TILE + sub * kBT;
+  const int t0 = r * T + m * VA_TILE + sub * kKeys;
   if (t0 >= row_end) return;  // workgroup-uniform: the schedule tile is ragged
-  const int t_last = min(t0 + kBT, row_end) - 1;
+  const int t_last = min(t0 + kKeys, row_end) - 1;
   const int ib_lo = t0 / kBS;
 
   const size_t row_bytes = (size_t)hq * d * 2;
@@ -281,18 +298,22 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const size_t total = (size_t)N * row_bytes;
   const buffer_t qbuf = make_buffer((const char *)Q + base_off, total - base_off);
   const buffer_t gbuf = make_buffer((const char *)dO + base_off, total - base_off);
-  // HBM -> LDS copy of a 64-row block: 16 transfers of 1 KB (4 rows) per tensor, two per wave
-  const int dma_row = wave * 4 + (lane >> 4);  // and 32 rows further for the second transfer (same swizzle)
+  // HBM -> LDS copy of a 64-row block: 16 transfers of 1 KB (4 rows) per tensor and sub-block, shared
+  // out over the waves (transfers of one wave are 4 kWaves rows apart: the same swizzle)
+  const int dma_row = wave * 4 + (lane >> 4);
   const uint32_t dma_off = dma_lane_offset(lane, dma_row, row_bytes, 0, d);
-  const bool dma_ok = dma_lane_ok(lane, dma_row, d);
+  bool dma_ok[kHf];
+#pragma unroll
+  for (int hf = 0; hf < kHf; ++hf) dma_ok[hf] = dma_lane_ok(lane, dma_row, d - 128 * hf);
   const uint32_t blk_bytes = (uint32_t)(kBS * row_bytes);
-  const uint32_t p_bytes = (uint32_t)(32 * row_bytes);
+  const uint32_t p_bytes = (uint32_t)(4 * kWaves * row_bytes);
   typedef __attribute__((address_space(3))) void *lds_void;
   const int stat_row = threadIdx.x & (kBS - 1);
   const bool stat_is_lse = (threadIdx.x & kBS) == 0;
   const float *stat_src = stat_is_lse ? LSE : delta;
   const float stat_mul = stat_is_lse ? -1.f / scale : -1.f;
   float rstat = 0.f;
+  uint16_t *const S0 = stages, *const S1 = stages + kStage;
   auto copy_block = [&](uint16_t *dst, int hh, int ib) {
     {  // every thread loads (a load under a condition would be waited for at the end of the branch)
       const int i = min(ib * kBS + stat_row, N - 1);
@@ -300,21 +321,23 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
     }
     const uint32_t off = dma_off + (uint32_t)(ib - ib_lo) * blk_bytes + (uint32_t)((g * G + hh) * d * 2);
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-      const uint32_t o = dma_ok ? off + p * p_bytes : kPastEnd;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(qbuf, (lds_void)(dst + (8 * p + wave) * 512), 16, o, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(gbuf, (lds_void)(dst + kBlk + (8 * p + wave) * 512), 16, o, 0, 0, 0);
-    }
+    for (int hf = 0; hf < kHf; ++hf)
+#pragma unroll
+      for (int p = 0; p < 16 / kWaves; ++p) {
+        const uint32_t o = dma_ok[hf] ? off + p * p_bytes + hf * 256 : kPastEnd;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(qbuf, (lds_void)(dst + hf * kBlk + (kWaves * p + wave) * 512), 16, o, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(gbuf, (lds_void)(dst + kBlkT + hf * kBlk + (kWaves * p + wave) * 512), 16, o, 0, 0, 0);
+      }
   };
   auto put_stats = [&](uint16_t *dst) {
-    if (threadIdx.x < 2 * kBS) ((float *)(dst + 2 * kBlk))[threadIdx.x] = rstat * stat_mul;
+    if (threadIdx.x < 2 * kBS) ((float *)(dst + 2 * kBlkT))[threadIdx.x] = rstat * stat_mul;
   };
-  uint16_t *S0 = stages, *S1 = stages + kStage;
   copy_block(S0, 0, ib_lo);  // needs nothing but the tile: in flight while the bounds arrive
 
   // Everything else the prologue needs depends on the tile only: all of it is requested before any
   // of it is looked at (a value made wave-uniform right after its load would hold the next load
   // back by a full memory round trip, four times in a row).
+  uint16_t *const kv_tile = kKvInStage ? S1 : kv_own;  // K sub-blocks, then V sub-blocks
   const int jw0 = t0 + kg * 32;
   const int jw1 = min(jw0 + 31, t_last);
   const bool wave_ok = jw0 <= t_last;
@@ -326,19 +349,21 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const int se_min_v = seg_end[min(jw0, t_last)];
   const int se_max_v = seg_end[jw1 < jw0 ? t_last : jw1];
   const int se_j_v = seg_end[j_ld];
-  {  // K and V rows t0 .. t0 + 127 of head g -> kv_tile: 32 transfers of 4 rows per tensor, 4 per wave
+  {  // K and V rows t0 .. t0 + kKeys - 1 of head g -> kv_tile: 4 transfers of 4 rows per wave, tensor and sub-block
     const size_t kv_row_bytes = (size_t)hkv * d * 2;
     const size_t kv_off = (size_t)t0 * kv_row_bytes, kv_total = (size_t)N * kv_row_bytes;
     const buffer_t kb = make_buffer((const char *)K + kv_off, kv_total - kv_off);
     const buffer_t vb = make_buffer((const char *)V + kv_off, kv_total - kv_off);
     const uint32_t o0 = dma_lane_offset(lane, dma_row, kv_row_bytes, g, d);
-    const uint32_t step = (uint32_t)(32 * kv_row_bytes);
+    const uint32_t step = (uint32_t)(4 * kWaves * kv_row_bytes);
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
-      const uint32_t o = dma_ok ? o0 + p * step : kPastEnd;
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(kb, (lds_void)(kv_tile + (8 * p + wave) * 512), 16, o, 0, 0, 0);
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(vb, (lds_void)(kv_tile + kBT * kD + (8 * p + wave) * 512), 16, o, 0, 0, 0);
-    }
+    for (int hf = 0; hf < kHf; ++hf)
+#pragma unroll
+      for (int p = 0; p < 4; ++p) {
+        const uint32_t o = dma_ok[hf] ? o0 + p * step + hf * 256 : kPastEnd;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(kb, (lds_void)(kv_tile + hf * kKvSub + (kWaves * p + wave) * 512), 16, o, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(vb, (lds_void)(kv_tile + (kHf + hf) * kKvSub + (kWaves * p + wave) * 512), 16, o, 0, 0, 0);
+      }
   }
 
   const int ib_hi = (uniform(se_last_v) - 1) / kBS;  // query blocks end with the example of the tile's last key
@@ -369,7 +394,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 #pragma unroll
     for (int s2 = 0; s2 < 2; ++s2)
 #pragma unroll
-      for (int cb = 0; cb < kCb; ++cb) ty[s2][cb] = swz_read_tr<E>(Ys, tr_lane, cb, row0 + s2 * 16);
+      for (int cb = 0; cb < kCb; ++cb) ty[s2][cb] = swz_read_tr<E>(Ys + (cb >> 2) * kBlk, tr_lane, cb & 3, row0 + s2 * 16);
   };
   auto first_product = [&](f32x16 &x, const uint16_t *__restrict__ Xs, const float *__restrict__ st, int row0) {
 #pragma unroll
@@ -380,7 +405,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
     }
     x8 ax[kKs];
 #pragma unroll
-    for (int ks = 0; ks < kKs; ++ks) ax[ks] = swz_read_row<E>(Xs, row_lane, ks, row0);
+    for (int ks = 0; ks < kKs; ++ks) ax[ks] = swz_read_row<E>(Xs + (ks >> 3) * kBlk, row_lane, ks & 7, row0);
 #pragma unroll
     for (int ks = 0; ks < kKs; ++ks) x = mfma32(ax[ks], rf[ks], x);  // S - LSE / scale, or dP - D
   };
@@ -394,8 +419,8 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   auto v_step = [&](const uint16_t *__restrict__ cur, int il, int row0, int pw) {
     f32x16 x;
     x8 ty[2][kCb];
-    first_product(x, cur, (const float *)(cur + 2 * kBlk), row0);
-    read_ty(ty, cur + kBlk, row0);
+    first_product(x, cur, (const float *)(cur + 2 * kBlkT), row0);
+    read_ty(ty, cur + kBlkT, row0);
 #pragma unroll
     for (int v = 0; v < 16; ++v) x[v] = __builtin_amdgcn_exp2f(x[v] * scale_log2);  // P
     const bool interior = wave_full && il >= jw1 && il + 31 < se_min;
@@ -444,15 +469,15 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   bool act_b = false;  // K side: sub-block b of the previous block is waiting for its P
   auto k_iteration = [&](int it, const uint16_t *__restrict__ cur, uint16_t *__restrict__ nxt) {
     const int i0 = begin_block(it, nxt);
-    const float *st = (const float *)(cur + 2 * kBlk) + kBS;
+    const float *st = (const float *)(cur + 2 * kBlkT) + kBS;
     const bool act0 = is_active(i0), act1 = is_active(i0 + 32);
     // step 2 it: dP of sub-block a; dS, dK of the previous block's b (P at parity 1)
-    if (act0) first_product(xa, cur + kBlk, st, 0);
+    if (act0) first_product(xa, cur + kBlkT, st, 0);
     if (act_b) k_finish(xb, tyb, 1);
     lds_barrier();
     // step 2 it + 1: dP of sub-block b; dS, dK of a (P at parity 0)
     if (act1) {
-      first_product(xb, cur + kBlk, st, 32);
+      first_product(xb, cur + kBlkT, st, 32);
       read_ty(tyb, cur, 32);
     }
     if (act0) {
@@ -467,7 +492,9 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   wait_all_loads();
   lds_barrier();
 #pragma unroll
-  for (int ks = 0; ks < kKs; ++ks) rf[ks] = swz_read_row<E>(kv_tile + (k_side ? kBT * kD : 0), row_lane, ks, kg * 32);
+  for (int ks = 0; ks < kKs; ++ks)
+    rf[ks] = swz_read_row<E>(kv_tile + ((k_side ? kHf : 0) + (ks >> 3)) * kKvSub, row_lane, ks & 7, kg * 32);
+  if (kKvInStage) lds_barrier();  // every wave has its rows before stage 1 receives its first block
   VA_TRACE_T(tr1);
   if (!k_side) {
     for (int it = 0; it < n_it; it += 2) {  // bounds are workgroup-uniform: barriers stay aligned
@@ -504,11 +531,11 @@ static void launch_bwd_t(const uint16_t *g, const uint16_t *q, const uint16_t *k
     dq_mfma_kernel<E, EOut, kDh><<<gq, 256, 0, stream>>>(g, q, k, v, o, LSE, delta, dQ, seg.seg_start,
                                                          seg.q_tile_order, N, T, tiles_per_row, hq, hkv, d,
                                                          scale_log2, scale);
-  if constexpr (kDh <= 128) {
-    if (stages & VA_STAGE_DKDV)
-      dkdv_mfma_kernel<E, EOut, kDh><<<gkv, kDkdvThreads, 0, stream>>>(g, q, k, v, LSE, delta, dK, dV, seg.seg_end,
-                                                                       seg.kv_tile_order, N, T, tiles_per_row, hq,
-                                                                       hkv, d, scale_log2, scale);
+  if (stages & VA_STAGE_DKDV) {
+    typedef DkdvShape<kDh> Shape;
+    dkdv_mfma_kernel<E, EOut, kDh><<<gkv * (Shape::kSubTiles / kSub), Shape::kThreads, 0, stream>>>(
+        g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, N, T, tiles_per_row, hq, hkv, d, scale_log2,
+        scale);
   }
 }
 
