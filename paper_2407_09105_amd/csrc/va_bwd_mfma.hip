@@ -234,8 +234,18 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 // head_dim above 128 (kDh = 256): operand and accumulator tiles are twice as large, so a workgroup is
 // 4 waves = (64-key tile, KV head), one wave per SIMD with 512 registers each; blocks are two
 // 128-column halves, and the tile's own K and V rows pass through the memory of the second stage.
-template <int kDh> struct DkdvShape {
-  static constexpr int kKg = kDh > 128 ? 2 : 4;         // key groups (of 32 keys) per workgroup
+// Two shapes for head_dim <= 128, chosen on the device from the longest example of the packed batch
+// (both are launched; the workgroups of the one that does not apply leave at once):
+//   large: 8 waves on a 128-key tile, one workgroup per CU: each streamed Q/dO block serves 128 keys
+//          (long examples: -6 % against the small shape on config 5);
+//   small: 4 waves on a 64-key tile, two workgroups per CU that hide each other's prologue, epilogue
+//          and barriers (short examples: -14 % on config 4, -4 % on config 3), at twice the block
+//          copies per matrix instruction.
+constexpr int kDkdvSmallBelow = 1024;  // longest example (tokens) below which the small shape runs
+template <int kDh, bool kSmall> struct DkdvShape {
+  static_assert(!(kSmall && kDh > 128), "head_dim above 128 has one shape");
+  static constexpr int kKg = (kDh > 128 || kSmall) ? 2 : 4;  // key groups (of 32 keys) per workgroup
+  static constexpr int kWgPerCu = kSmall ? 2 : 1;
   static constexpr int kWaves = 2 * kKg;                // V side + K side
   static constexpr int kThreads = 64 * kWaves;
   static constexpr int kKeys = 32 * kKg;                // keys per workgroup
@@ -246,21 +256,24 @@ __device__ __forceinline__ void lds_barrier() {  // LDS traffic of this wave don
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-template <class E, class EOut, int kDh>
-__global__ void __launch_bounds__(DkdvShape<kDh>::kThreads, 1)
+// select: 0 = run; 1 = run only if the longest example has kDkdvSmallBelow tokens or more; 2 = only
+// if it has fewer (meta[1] is the longest example's length, left there by the boundary scan).
+template <class E, class EOut, int kDh, bool kSmall>
+__global__ void __launch_bounds__((DkdvShape<kDh, kSmall>::kThreads), (DkdvShape<kDh, kSmall>::kWgPerCu))
 dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
                   const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
                   const float *__restrict__ LSE, const float *__restrict__ delta, void *__restrict__ dK,
                   void *__restrict__ dV, const int32_t *__restrict__ seg_end,
-                  const int32_t *__restrict__ kv_tile_order, int N, int T, int tiles_per_row, int hq,
-                  int hkv, int d, float scale_log2, float scale) {
+                  const int32_t *__restrict__ kv_tile_order, const int32_t *__restrict__ meta, int select,
+                  int N, int T, int tiles_per_row, int hq, int hkv, int d, float scale_log2, float scale) {
+  if (select != 0 && ((meta[1] < kDkdvSmallBelow) != (select == 2))) return;  // workgroup-uniform
   constexpr int kKs = kDh / 16, kCb = kDh / 32;
   constexpr int kHf = kDh > 128 ? 2 : 1;  // 128-column sub-blocks per block
   constexpr int kBlkT = kBlk * kHf;       // elements of one tensor's streamed block
-  typedef DkdvShape<kDh> Shape;
+  typedef DkdvShape<kDh, kSmall> Shape;
   constexpr int kKg = Shape::kKg, kWaves = Shape::kWaves, kKeys = Shape::kKeys, kSubTiles = Shape::kSubTiles;
   constexpr int kKvSub = kKeys * kD;      // elements of one sub-block of the tile's own K (or V) rows
-  constexpr bool kKvInStage = kHf > 1;    // no room for a kv_tile of its own: the rows pass through stage 1
+  constexpr bool kKvInStage = kHf > 1 || kSmall;  // no room for a kv_tile of its own: the rows pass through stage 1
   typedef typename E::x8 x8;
   // two stages of {Q block, dO block (swizzled), -LSE / scale [64], -D [64]}; reused as the staging
   // area of the result stores
@@ -521,6 +534,17 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 
 }  // namespace
 
+// compute units of the current device (256 on MI355X), asked for once
+static int compute_units() {
+  static const int n = [] {
+    int dev = 0, v = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
+      v = 256;
+    return v;
+  }();
+  return n;
+}
+
 template <class E, class EOut, int kDh>
 static void launch_bwd_t(const uint16_t *g, const uint16_t *q, const uint16_t *k, const uint16_t *v,
                          const uint16_t *o, const float *LSE, float *delta, void *dQ, void *dK, void *dV,
@@ -532,10 +556,27 @@ static void launch_bwd_t(const uint16_t *g, const uint16_t *q, const uint16_t *k
                                                          seg.q_tile_order, N, T, tiles_per_row, hq, hkv, d,
                                                          scale_log2, scale);
   if (stages & VA_STAGE_DKDV) {
-    typedef DkdvShape<kDh> Shape;
-    dkdv_mfma_kernel<E, EOut, kDh><<<gkv * (Shape::kSubTiles / kSub), Shape::kThreads, 0, stream>>>(
-        g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, N, T, tiles_per_row, hq, hkv, d, scale_log2,
-        scale);
+    typedef DkdvShape<kDh, false> Large;
+    const unsigned g_large = gkv * (Large::kSubTiles / kSub);
+    if constexpr (kDh <= 128) {
+      typedef DkdvShape<kDh, true> Small;
+      const unsigned g_small = gkv * (Small::kSubTiles / kSub);
+      // few workgroups per compute unit: the finer tiles of the small shape balance better whatever the
+      // example lengths (known on the host, so only one kernel is launched); otherwise both are
+      // launched and the device picks by the longest example
+      const bool few = g_large <= 4u * (unsigned)compute_units();
+      if (!few)
+        dkdv_mfma_kernel<E, EOut, kDh, false><<<g_large, Large::kThreads, 0, stream>>>(
+            g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, 1, N, T, tiles_per_row, hq, hkv,
+            d, scale_log2, scale);
+      dkdv_mfma_kernel<E, EOut, kDh, true><<<g_small, Small::kThreads, 0, stream>>>(
+          g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, few ? 0 : 2, N, T, tiles_per_row, hq,
+          hkv, d, scale_log2, scale);
+    } else {
+      dkdv_mfma_kernel<E, EOut, kDh, false><<<g_large, Large::kThreads, 0, stream>>>(
+          g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, 0, N, T, tiles_per_row, hq, hkv, d,
+          scale_log2, scale);
+    }
   }
 }
 
