@@ -1,4 +1,4 @@
-// Backward kernels: dQ (query-major) and dK/dV (key-major), bf16 / fp16, head_dim <= 128.
+// Backward kernels: dQ (query-major) and dK/dV (key-major), bf16 / fp16, head_dim <= 256.
 //
 // What they compute (see include/varlen_attn.h), from the saved LSE and D = rowsum(dO * O):
 //   P_ij = exp(scale q_i.k_j - LSE_i),  dP_ij = dO_i.v_j,  dS_ij = P_ij (dP_ij - D_i)
@@ -10,8 +10,8 @@
 //   dq_mfma_kernel   : workgroup = (128-query tile, query head); streams K/V blocks of 64 rows.
 //                      Lane owns a query row: S^T = K Q^T, dP^T = V dO^T, dQ^T += K^T dS^T.  It also
 //                      forms D for its rows and stores it for the other kernel, so it runs first.
-//   dkdv_mfma_kernel : workgroup = (128-key tile, KV head); streams Q/dO blocks of 64 rows of every
-//                      query head of the group.  Lane owns a key row: S = Q K^T, dP = dO V^T,
+//   dkdv_mfma_kernel : workgroup = (128- or 64-key tile, KV head); streams Q/dO blocks of 64 rows of
+//                      every query head of the group.  Lane owns a key row: S = Q K^T, dP = dO V^T,
 //                      dV^T += dO^T P, dK^T += Q^T dS; the dV and the dK halves run on different waves.
 // In both, the streamed index lies on the accumulator's register axis and feeds the last
 // contraction as a B operand straight from registers (see va_mfma_common.h).
@@ -32,8 +32,9 @@ VA_TRACE_DECL(g_trace_dkdv);
 
 // ---------------------------------------------------------------------------------------------
 // Template parameters of both kernels: E element type of the inputs (Bf16 / F16); EOut the
-// gradients' type (float, or E); kDh head_dim rounded up to 64, 96 or 128 (the unrolling); the
-// argument d is the tensors' head_dim (a multiple of 8, <= kDh).
+// gradients' type (float, or E); kDh head_dim rounded up to 64, 96, 128 or 256 (the unrolling); the
+// argument d is the tensors' head_dim (a multiple of 8, <= kDh).  With kDh = 256 a block is two
+// 128-column halves and the dQ kernel runs one workgroup per CU (accumulators in AGPRs).
 template <class E, class EOut, int kDh>
 __global__ void __launch_bounds__(256, kDh > 128 ? 1 : 2)
 dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
@@ -237,10 +238,10 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 // Two shapes for head_dim <= 128, chosen on the device from the longest example of the packed batch
 // (both are launched; the workgroups of the one that does not apply leave at once):
 //   large: 8 waves on a 128-key tile, one workgroup per CU: each streamed Q/dO block serves 128 keys
-//          (long examples: -6 % against the small shape on config 5);
+//          (examples of thousands of tokens: 6 % faster than the small shape);
 //   small: 4 waves on a 64-key tile, two workgroups per CU that hide each other's prologue, epilogue
-//          and barriers (short examples: -14 % on config 4, -4 % on config 3), at twice the block
-//          copies per matrix instruction.
+//          and barriers (examples of 8..128 tokens: 14 % faster), at twice the block copies per
+//          matrix instruction.
 constexpr int kDkdvSmallBelow = 1024;  // longest example (tokens) below which the small shape runs
 template <int kDh, bool kSmall> struct DkdvShape {
   static_assert(!(kSmall && kDh > 128), "head_dim above 128 has one shape");
