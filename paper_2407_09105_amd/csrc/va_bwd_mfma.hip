@@ -235,14 +235,14 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 // head_dim above 128 (kDh = 256): operand and accumulator tiles are twice as large, so a workgroup is
 // 4 waves = (64-key tile, KV head), one wave per SIMD with 512 registers each; blocks are two
 // 128-column halves, and the tile's own K and V rows pass through the memory of the second stage.
-// Two shapes for head_dim <= 128, chosen on the device from the longest example of the packed batch
-// (both are launched; the workgroups of the one that does not apply leave at once):
+// Two shapes for head_dim <= 128, chosen on the device from the mean example length of the packed
+// batch (both are launched; the workgroups of the one that does not apply leave at once):
 //   large: 8 waves on a 128-key tile, one workgroup per CU: each streamed Q/dO block serves 128 keys
 //          (examples of thousands of tokens: 6 % faster than the small shape);
 //   small: 4 waves on a 64-key tile, two workgroups per CU that hide each other's prologue, epilogue
 //          and barriers (examples of 8..128 tokens: 14 % faster), at twice the block copies per
 //          matrix instruction.
-constexpr int kDkdvSmallBelow = 1024;  // longest example (tokens) below which the small shape runs
+constexpr int kDkdvSmallBelow = 1024;  // mean example length (tokens) below which the small shape runs
 template <int kDh, bool kSmall> struct DkdvShape {
   static_assert(!(kSmall && kDh > 128), "head_dim above 128 has one shape");
   static constexpr int kKg = (kDh > 128 || kSmall) ? 2 : 4;  // key groups (of 32 keys) per workgroup
@@ -257,8 +257,8 @@ __device__ __forceinline__ void lds_barrier() {  // LDS traffic of this wave don
   asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 }
 
-// select: 0 = run; 1 = run only if the longest example has kDkdvSmallBelow tokens or more; 2 = only
-// if it has fewer (meta[1] is the longest example's length, left there by the boundary scan).
+// select: 0 = run; 1 = run only if the examples have kDkdvSmallBelow tokens or more on average; 2 =
+// only if they have fewer (meta[0] is the number of examples, left there by the boundary scan).
 template <class E, class EOut, int kDh, bool kSmall>
 __global__ void __launch_bounds__((DkdvShape<kDh, kSmall>::kThreads), (DkdvShape<kDh, kSmall>::kWgPerCu))
 dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
@@ -267,7 +267,7 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
                   void *__restrict__ dV, const int32_t *__restrict__ seg_end,
                   const int32_t *__restrict__ kv_tile_order, const int32_t *__restrict__ meta, int select,
                   int N, int T, int tiles_per_row, int hq, int hkv, int d, float scale_log2, float scale) {
-  if (select != 0 && ((meta[1] < kDkdvSmallBelow) != (select == 2))) return;  // workgroup-uniform
+  if (select != 0 && (((long long)N < (long long)kDkdvSmallBelow * meta[0]) != (select == 2))) return;  // workgroup-uniform
   constexpr int kKs = kDh / 16, kCb = kDh / 32;
   constexpr int kHf = kDh > 128 ? 2 : 1;  // 128-column sub-blocks per block
   constexpr int kBlkT = kBlk * kHf;       // elements of one tensor's streamed block
@@ -535,17 +535,6 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 
 }  // namespace
 
-// compute units of the current device (256 on MI355X), asked for once
-static int compute_units() {
-  static const int n = [] {
-    int dev = 0, v = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v <= 0)
-      v = 256;
-    return v;
-  }();
-  return n;
-}
-
 template <class E, class EOut, int kDh>
 static void launch_bwd_t(const uint16_t *g, const uint16_t *q, const uint16_t *k, const uint16_t *v,
                          const uint16_t *o, const float *LSE, float *delta, void *dQ, void *dK, void *dV,
@@ -562,17 +551,13 @@ static void launch_bwd_t(const uint16_t *g, const uint16_t *q, const uint16_t *k
     if constexpr (kDh <= 128) {
       typedef DkdvShape<kDh, true> Small;
       const unsigned g_small = gkv * (Small::kSubTiles / kSub);
-      // few workgroups per compute unit: the finer tiles of the small shape balance better whatever the
-      // example lengths (known on the host, so only one kernel is launched); otherwise both are
-      // launched and the device picks by the longest example
-      const bool few = g_large <= 4u * (unsigned)compute_units();
-      if (!few)
-        dkdv_mfma_kernel<E, EOut, kDh, false><<<g_large, Large::kThreads, 0, stream>>>(
-            g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, 1, N, T, tiles_per_row, hq, hkv,
-            d, scale_log2, scale);
+      // nothing about the lengths is known on the host: both are launched and the device picks
+      dkdv_mfma_kernel<E, EOut, kDh, false><<<g_large, Large::kThreads, 0, stream>>>(
+          g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, 1, N, T, tiles_per_row, hq, hkv, d,
+          scale_log2, scale);
       dkdv_mfma_kernel<E, EOut, kDh, true><<<g_small, Small::kThreads, 0, stream>>>(
-          g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, few ? 0 : 2, N, T, tiles_per_row, hq,
-          hkv, d, scale_log2, scale);
+          g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, 2, N, T, tiles_per_row, hq, hkv, d,
+          scale_log2, scale);
     } else {
       dkdv_mfma_kernel<E, EOut, kDh, false><<<g_large, Large::kThreads, 0, stream>>>(
           g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, 0, N, T, tiles_per_row, hq, hkv, d,
