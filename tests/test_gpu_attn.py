@@ -67,6 +67,7 @@ MFMA_CASES = [
     ([[100, 219], [319], [1] * 319], 2, 2),               # 3 rows, T = 319 (not a multiple of 64)
     ([[513, 31, 480]], 5, 1),                             # G = 5 (not a power of two), 1024 tokens
     ([[17] * 30 + [2]], 2, 2),                            # many short examples per tile
+    ([[1100, 1030]], 2, 1),                               # mean example length >= 1024: the dK/dV kernel's large shape
 ]
 
 
