@@ -311,6 +311,55 @@ def read_traffic(cfg_id, kernel):
     return None
 
 
+KERNEL_NAMES = {"fwd": "fwd_mfma_kernel", "bwd_dKdV": "dkdv_mfma_kernel", "bwd_dQ": "dq_mfma_kernel"}
+
+
+def algorithmic_work(cfg, pairs, e=2, eg=2):
+    """Per launch and kernel: (algorithmic FLOPs, algorithmic HBM bytes).
+    FLOPs per unmasked pair per query head: forward 4d; the backward's 10d split as 8d to the dK/dV
+    kernel (S, dP, dV, dK) and 2d to the dQ kernel (dQ; its own recomputation of S and dP is overhead,
+    not algorithmic work).  Bytes: every operand and result of the kernel once (e bytes per input
+    element, eg per gradient element, 4 per row statistic)."""
+    n, d, hq, hkv = cfg.n_tokens, cfg.d, cfg.hq, cfg.hkv
+    ph = pairs * hq
+    return {
+        # reads Q, K, V; writes O and the row log-sum-exp
+        "fwd": (4 * d * ph, n * (e * d * (2 * hq + 2 * hkv) + 4 * hq)),
+        # reads Q, dO, K, V, LSE, D; writes dK, dV
+        "bwd_dKdV": (8 * d * ph, n * (e * d * (2 * hq + 2 * hkv) + eg * d * 2 * hkv + 8 * hq)),
+        # reads Q, dO, O, K, V, LSE; writes dQ and D
+        "bwd_dQ": (2 * d * ph, n * (e * d * (3 * hq + 2 * hkv) + eg * d * hq + 8 * hq)),
+    }
+
+
+def roofline_of(cfg, pairs, stages, cfg_id):
+    """Roofline object of the kernel with the longest average launch.  The bound is the one the
+    kernel's algorithmic intensity selects: below the ridge (bf16 MFMA peak / HBM peak, in FLOP per
+    byte) the launch cannot beat the time its algorithmic bytes take, above it the time of its FLOPs."""
+    work = algorithmic_work(cfg, pairs)
+    dom = max(work, key=lambda s: stages[s])
+    fl, by = work[dom]
+    sec = stages[dom] * 1e-3
+    ridge = PEAK_BF16_MFMA_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9)
+    if fl / by >= ridge:
+        bound, achieved, peak, unit = "mfma", fl / sec / 1e12, PEAK_BF16_MFMA_TFLOPS, "TFLOP/s"
+    else:
+        bound, achieved, peak, unit = "hbm", by / sec / 1e9, PEAK_HBM_GBS, "GB/s"
+    return {
+        "kernel": KERNEL_NAMES[dom], "bound": bound, "achieved": achieved, "peak": peak, "unit": unit,
+        "frac": achieved / peak, "traffic": read_traffic(cfg_id, KERNEL_NAMES[dom]),
+        "avg_kernel_ms": stages[dom],
+        "algorithmic_flops": fl, "algorithmic_bytes": by, "flop_per_byte": fl / by, "ridge_flop_per_byte": ridge,
+        "all_kernels": {KERNEL_NAMES[s]: {"ms": stages[s],
+                                          "algorithmic_TFLOPs": work[s][0] / (stages[s] * 1e-3) / 1e12,
+                                          "frac_of_bf16_mfma_peak": work[s][0] / (stages[s] * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS,
+                                          "algorithmic_GBs": work[s][1] / (stages[s] * 1e-3) / 1e9,
+                                          "frac_of_hbm_peak": work[s][1] / (stages[s] * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                                          "flop_per_byte": work[s][0] / work[s][1]}
+                        for s in work},
+    }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -348,23 +397,7 @@ def main():
     useful = f_fwd + f_bwd
     value = useful / (ms_plain * 1e-3) / 1e12
 
-    # dominant kernel -> roofline.  Algorithmic FLOPs per pair per head: forward 4d; the backward's
-    # 10d split as 8d to the dK/dV kernel (S, dP, dV, dK) and 2d to the dQ kernel (dQ; its own
-    # recomputation of S and dP is overhead, not algorithmic work).
-    pairs_h = w.stats["pairs"] * cfg.hq
-    algo = {"fwd": 4 * cfg.d * pairs_h, "bwd_dKdV": 8 * cfg.d * pairs_h, "bwd_dQ": 2 * cfg.d * pairs_h}
-    kernel_names = {"fwd": "fwd_mfma_kernel", "bwd_dKdV": "dkdv_mfma_kernel", "bwd_dQ": "dq_mfma_kernel"}
-    dom = max(algo, key=lambda s: stages[s])
-    achieved = algo[dom] / (stages[dom] * 1e-3) / 1e12
-    roofline = {
-        "kernel": kernel_names[dom], "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_MFMA_TFLOPS,
-        "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_MFMA_TFLOPS,
-        "traffic": read_traffic(cfg_id, kernel_names[dom]),
-        "avg_kernel_ms": stages[dom],
-        "all_kernels": {kernel_names[s]: {"ms": stages[s], "algorithmic_TFLOPs": algo[s] / (stages[s] * 1e-3) / 1e12,
-                                          "frac_of_bf16_mfma_peak": algo[s] / (stages[s] * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS}
-                        for s in algo},
-    }
+    roofline = roofline_of(cfg, w.stats["pairs"], stages, cfg_id)
     # minimum HBM traffic of the whole step (each tensor once) -> fraction of the HBM roofline
     e = 2
     hbm_min = cfg.n_tokens * (6 * e * cfg.d * (cfg.hq + cfg.hkv) + 12 * cfg.hq)

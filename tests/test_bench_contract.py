@@ -30,10 +30,33 @@ def test_flop_accounting_counts_unmasked_pairs():
     assert w2.stats["pairs"] == sum(L * (L + 1) // 2 for L in w2.lengths[0])
 
 
+def test_roofline_bound_follows_algorithmic_intensity():
+    # configs 2 and 5: the slowest kernel (dK/dV) lies above the ridge of 2500 TFLOP/s over 8 TB/s -> MFMA-bound,
+    # quoted in TFLOP/s; config 4 (examples of 8..128 tokens) lies far below it -> HBM-bound, quoted in GB/s
+    stages = {"pack": 0.01, "fwd": 0.1, "bwd_dQ": 0.15, "bwd_dKdV": 0.25}
+    for cfg_id, bound, unit, peak in ((2, "mfma", "TFLOP/s", 2500.0), (5, "mfma", "TFLOP/s", 2500.0), (4, "hbm", "GB/s", 8000.0)):
+        w = wl.make_workload(cfg_id, tensors=False)
+        r = bench.roofline_of(w.cfg, w.stats["pairs"], stages, cfg_id)
+        assert (r["kernel"], r["bound"], r["unit"], r["peak"]) == ("dkdv_mfma_kernel", bound, unit, peak)
+        assert abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-12
+        c, pairs = w.cfg, w.stats["pairs"]
+        assert r["algorithmic_flops"] == 8 * c.d * c.hq * pairs
+        # Q, dO read; K, V read; dK, dV written (2 bytes each); LSE and D read (4 bytes each)
+        assert r["algorithmic_bytes"] == c.n_tokens * (2 * c.d * (2 * c.hq + 4 * c.hkv) + 8 * c.hq)
+        want = r["algorithmic_flops"] / 0.25e-3 / 1e12 if bound == "mfma" else r["algorithmic_bytes"] / 0.25e-3 / 1e9
+        assert abs(r["achieved"] - want) < 1e-9 * want
+    # the three kernels' FLOPs add up to the useful FLOPs of the step
+    w = wl.make_workload(2, tensors=False)
+    work = bench.algorithmic_work(w.cfg, w.stats["pairs"])
+    assert sum(f for f, _ in work.values()) == sum(bench.flops(w.cfg, w.stats["pairs"]))
+
+
 def test_traffic_summary_is_readable():
     for kernel in ("fwd_mfma_kernel", "dq_mfma_kernel", "dkdv_mfma_kernel"):
         t = bench.read_traffic(2, kernel)
         assert t is not None and 2.0e8 < t < 2.0e9, kernel     # bytes per launch on config 2
+        t4 = bench.read_traffic(4, kernel)
+        assert t4 is not None and 2.0e9 < t4 < 5.0e9, kernel   # config 4: 65536 tokens
     assert bench.read_traffic(2, "no_such_kernel") is None
 
 
