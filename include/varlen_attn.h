@@ -142,9 +142,9 @@ size_t va_attn_workspace_bytes(int32_t n_tokens, int32_t hq, int32_t hkv, int32_
  * (the varlen attention routine the paper's Section 3 hands cu_seqlens to; the mask is
  * Table 1's "correct cross-attention").  Only key tiles that intersect an example's
  * causal triangle are visited.
- *   dt            : element type of Q, K, V, O.  VA_BF16 and VA_F16 with d a multiple of 8 up to 128
- *                   run the MFMA kernels (unrolled for d = 64, 96, 128; a smaller d is padded with
- *                   zero columns on the fly); other (dt, d <= 256) combinations run a plain
+ *   dt            : element type of Q, K, V, O.  VA_BF16 and VA_F16 with d a multiple of 8 up to 256
+ *                   run the MFMA kernels (unrolled for d = 64, 96, 128, 256; a smaller d is padded
+ *                   with zero columns on the fly); other (dt, d <= 256) combinations run a plain
  *                   fp32-arithmetic kernel.
  *   softmax_scale : <= 0 means 1 / sqrt(d).
  *   workspace     : >= va_attn_workspace_bytes(..., 0) bytes (may be NULL when that is 0).

@@ -41,7 +41,7 @@ hipError_t launch_generic_bwd(const void *dO, const void *Q, const void *K, cons
                               va_dtype grad_dt, const va_segments &seg, int N, int hq, int hkv,
                               int d, va_dtype dt, float scale, hipStream_t stream, unsigned stages);
 
-// va_fwd_mfma.hip / va_bwd_mfma.hip : bf16 / fp16, head_dim a multiple of 8 up to 128
+// va_fwd_mfma.hip / va_bwd_mfma.hip : bf16 / fp16, head_dim a multiple of 8 up to 256
 hipError_t launch_mfma_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
                            const va_segments &seg, int rows, int T, int hq, int hkv, int d, va_dtype dt,
                            float scale, hipStream_t stream);

@@ -1,4 +1,4 @@
-// Shared device helpers of the MFMA kernels (bf16 / fp16, head_dim <= 128, gfx950).
+// Shared device helpers of the MFMA kernels (bf16 / fp16, head_dim <= 256, gfx950).
 //
 // Matrix-core tile used throughout: v_mfma_f32_32x32x16_{bf16,f16}, D[32x32] += A[32x16] * B[16x32].
 // Register layout per 64-lane wave (lane l, half = l / 32):
