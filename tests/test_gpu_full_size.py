@@ -138,3 +138,52 @@ def test_padded_batch_equals_packed_at_real_tokens():
         assert float((x - y).abs().max()) <= 2e-2
         assert float((x - y).norm() / x.norm()) <= 5e-3
     assert float((lse[:, ir] - lsep[:, ip]).abs().max()) <= 1e-3
+
+
+def test_byte_offsets_up_to_the_32bit_limit():
+    # One packed row = one example of 3800 tokens with 2040 heads of 256: consecutive tokens are 1 MiB apart, so
+    # the 32-bit byte offsets the MFMA kernels hand to their buffer loads run up to 3.98e9 (token 2048 sits at 2^31
+    # exactly) -- just under the largest size the library accepts; one token more per row is refused.
+    T, H, d = 3800, 2040, 256
+    assert (T + 256) * H * d * 2 < 0xffffff00 <= (T + 256 + 64) * H * d * 2
+    g = torch.Generator(device=DEV)
+    g.manual_seed(4242)
+    mk = lambda: torch.randn((T, H, d), device=DEV, generator=g, dtype=torch.float32).to(torch.bfloat16)
+    q, k, v, do = mk(), mk(), mk(), mk()
+    pos = torch.arange(T, dtype=torch.int64, device=DEV)[None, :]
+    seg = binding.pack_to_cu_seqlens(pos)
+    o, lse = binding.varlen_attn_fwd(q, k, v, seg)
+    dq, dk, dv = binding.varlen_attn_bwd(do, q, k, v, o, lse, seg)      # gradients stored in bf16
+    torch.cuda.synchronize()
+    cu = np.array([0, T], dtype=np.int32)
+    assert np.array_equal(seg.host()["cu_seqlens"], cu)
+
+    heads = [0, 1, 1019, 2038, 2039]                                    # the oracle sees these heads only
+    hs = torch.tensor(heads, device=DEV)
+    f = lambda t: t.float().cpu().numpy().astype(np.float64)
+    qs, ks, vs, dos = (f(t[:, hs]) for t in (q, k, v, do))
+    tok = np.array([0, 1, 31, 32, 127, 128, 2047, 2048, 2049, 3071, 3799, 3798, 3711, 3712], dtype=np.int32)
+    tt = np.repeat(tok, len(heads))
+    hh = np.tile(np.arange(len(heads), dtype=np.int32), len(tok))
+    Or, LSEr, dQr = oracle.rows_q(dos, qs, ks, vs, cu, tt, hh)
+    dKr, dVr = oracle.rows_kv(dos, qs, ks, vs, cu, tt, hh)
+    ti = torch.from_numpy(tt.astype(np.int64)).to(DEV)
+    hi = hs[torch.from_numpy(hh.astype(np.int64)).to(DEV)]
+    got = {"O": f(o[ti, hi]), "dQ": f(dq[ti, hi]), "dK": f(dk[ti, hi]), "dV": f(dv[ti, hi])}
+    ref = {"O": Or, "dQ": dQr, "dK": dKr, "dV": dVr}
+    for key in got:
+        assert rel_l2(got[key], ref[key]) <= BF16_REL_L2, key
+        bound = BF16_MAX_ABS + (np.abs(ref[key]) / 256.0 if key != "O" else 0.0)   # bf16-stored gradients
+        assert (np.abs(got[key] - ref[key]) <= bound).all(), (key, max_abs(got[key], ref[key]))
+    assert max_abs(f(lse[hi, ti]), LSEr) <= 1e-3
+    for t in (o, lse, dq, dk, dv):
+        assert bool(torch.isfinite(t).all())
+
+    # 64 tokens more per row: refused on the host, nothing is launched
+    T2 = T + 64
+    pos2 = torch.arange(T2, dtype=torch.int64, device=DEV)[None, :]
+    seg2 = binding.pack_to_cu_seqlens(pos2)
+    del o, lse, dq, dk, dv
+    q2 = torch.zeros((T2, H, d), device=DEV, dtype=torch.bfloat16)
+    with pytest.raises(RuntimeError):
+        binding.varlen_attn_fwd(q2, q2, q2, seg2)
