@@ -31,7 +31,9 @@ def _check_orders(got, pos_np):
     cost_kv = ((se[t1] - 1) >> 6) - (t0 >> 6) + 1
 
     def key(length, start, cost):
-        return (np.minimum(length, (1 << 20) - 1) << 43) | ((0x7FFFFFFF - start) << 12) | np.minimum(cost, 4095)
+        # examples of at most one schedule tile all rank alike (they stay in stream order), longer ones by length
+        rank = np.where(length <= TILE, 0, np.minimum(length, (1 << 20) - 1))
+        return (rank << 43) | ((0x7FFFFFFF - start) << 12) | np.minimum(cost, 4095)
 
     key_q = key(se[t0] - ss[t0], ss[t0], cost_q)       # governed by the example of the tile's first token
     key_kv = key(se[t1] - ss[t1], ss[t1], cost_kv)     # ... of its last token
