@@ -100,7 +100,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 #pragma unroll
       for (int p = 0; p < 8; ++p) {
         const uint32_t o = dma_ok[hf] ? tile_off + p * (uint32_t)(16 * q_row_bytes) + hf * 256 : kPastEnd;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (lds_void)(dst + hf * kTileSub + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(xb, (lds_void)(dst + hf * kTileSub + (4 * p + wave) * 512), 16, o, 0, 0, kOnce);
       }
   };
   copy_tile(Q, K0);
@@ -375,8 +375,8 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 #pragma unroll
       for (int p = 0; p < 4; ++p) {
         const uint32_t o = dma_ok[hf] ? o0 + p * step + hf * 256 : kPastEnd;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(kb, (lds_void)(kv_tile + hf * kKvSub + (kWaves * p + wave) * 512), 16, o, 0, 0, 0);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(vb, (lds_void)(kv_tile + (kHf + hf) * kKvSub + (kWaves * p + wave) * 512), 16, o, 0, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(kb, (lds_void)(kv_tile + hf * kKvSub + (kWaves * p + wave) * 512), 16, o, 0, 0, kOnce);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(vb, (lds_void)(kv_tile + (kHf + hf) * kKvSub + (kWaves * p + wave) * 512), 16, o, 0, 0, kOnce);
       }
   }
 
