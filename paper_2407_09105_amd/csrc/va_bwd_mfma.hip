@@ -398,6 +398,14 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   u32x4 *const ex = exch + kg * 256 + lane;  // + parity * 128 + part * 64
 
   x8 rf[kKs];  // this lane's key row: K (the V side computes S) or V (the K side computes dP); set below
+  // Order of the streamed blocks.  One query head per KV head: ib_lo, ib_lo + 1, ... ib_hi; neighbouring
+  // key tiles of an example, which run next to each other on one XCD, then follow each other two steps
+  // apart and find the blocks in L2.  Grouped heads: block ib_lo (the tile's own first rows; needs no
+  // bounds, so its copy is in flight while they arrive) for every head of the group, then blocks ib_hi,
+  // ib_hi - 1, ... ib_lo + 1, each for every head: the key tiles of one example share ib_hi, so they
+  // stream the same block at about the same time, whereas ascending they would run 2 G steps apart per
+  // tile and the blocks would have left the L2 (measured traffic of the kernel with 5 query heads per KV
+  // head and examples of thousands of tokens: 3.8 GB ascending, 2.9 GB this way; the same run time).
   int ib_cur = ib_lo, ib_nxt = ib_lo, hh_nxt = 0;
   // The K side runs one sub-block behind the V side: in step k the V side computes S(k), P(k) (left in
   // LDS) and dV(k), the K side computes dP(k) and, with the P(k-1) published by the previous barrier,
@@ -458,7 +466,10 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   bool more = false;
   auto begin_block = [&](int it, uint16_t *__restrict__ nxt) {  // returns the block's first query
     more = it + 1 < n_it;  // workgroup-uniform
-    if (++ib_nxt > ib_hi) { ib_nxt = ib_lo; ++hh_nxt; }
+    if (++hh_nxt == G) {  // all heads of the group have had this block
+      hh_nxt = 0;
+      ib_nxt = G == 1 ? ib_nxt + 1 : ib_nxt == ib_lo ? ib_hi : ib_nxt - 1;
+    }
     if (more) copy_block(nxt, hh_nxt, ib_nxt);
     const int i0 = ib_cur * kBS;
     ib_cur = ib_nxt;
