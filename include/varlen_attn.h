@@ -65,7 +65,8 @@ typedef struct va_segments {
   int32_t *seg_end;       /* [N]  one past its last token      (= cu[seg_id[t] + 1])                     */
   int32_t *meta;          /* [8]  meta[0] = n (examples), meta[1] = max_seqlen; rest reserved            */
   int32_t *q_tile_order;  /* [R * ceil(T / VA_TILE)] query tiles: tiles of the longest examples first,   */
-  int32_t *kv_tile_order; /* ... key tiles likewise; tiles of one example adjacent, heaviest first       */
+  int32_t *kv_tile_order; /* ... key tiles likewise; tiles of one example adjacent, heaviest first;      */
+                          /* tiles of examples of at most VA_TILE tokens come last, in stream order      */
   int32_t *scratch;       /* internal: per-chunk partial scans and tile costs                            */
 } va_segments;
 
