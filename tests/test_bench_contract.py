@@ -57,6 +57,8 @@ def test_traffic_summary_is_readable():
         assert t is not None and 2.0e8 < t < 2.0e9, kernel     # bytes per launch on config 2
         t4 = bench.read_traffic(4, kernel)
         assert t4 is not None and 2.0e9 < t4 < 5.0e9, kernel   # config 4: 65536 tokens
+        for cfg_id in (3, 5):
+            assert (bench.read_traffic(cfg_id, kernel) or 0) > 2.0e8, (cfg_id, kernel)
     assert bench.read_traffic(2, "no_such_kernel") is None
 
 
