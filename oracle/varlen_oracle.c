@@ -197,7 +197,11 @@ int oracle_fwd(const double *Q, const double *K, const double *V, const int32_t 
             const int g = h / G;
             double *S = (double *)malloc(sizeof(double) * (size_t)(b - a));
             double *P = (double *)malloc(sizeof(double) * (size_t)(b - a));
-            if (!S || !P) { bad = 1; free(S); free(P); continue; }
+            if (!S || !P) {
+#pragma omp atomic write
+                bad = 1;
+                free(S); free(P); continue;
+            }
             for (int64_t i = a; i < b; ++i) {
                 LSE[(size_t)h * N + i] = softmax_row(Q, K, i, a, h, g, Hq, Hkv, d, scale, S, P);
                 double *o = O + ((size_t)i * Hq + h) * d;
@@ -236,7 +240,11 @@ int oracle_bwd(const double *dO, const double *Q, const double *K, const double 
             double *P = (double *)malloc(sizeof(double) * L);
             double *dP = (double *)malloc(sizeof(double) * L);
             double *dS = (double *)malloc(sizeof(double) * L);
-            if (!S || !P || !dP || !dS) { bad = 1; free(S); free(P); free(dP); free(dS); continue; }
+            if (!S || !P || !dP || !dS) {
+#pragma omp atomic write
+                bad = 1;
+                free(S); free(P); free(dP); free(dS); continue;
+            }
             for (int h = g * G; h < (g + 1) * G; ++h) {
                 for (int64_t i = a; i < b; ++i) {
                     softmax_row(Q, K, i, a, h, g, Hq, Hkv, d, scale, S, P);
@@ -291,14 +299,22 @@ int oracle_rows_q(const double *dO, const double *Q, const double *K, const doub
     for (int r = 0; r < m; ++r) {
         const int64_t i = tok[r];
         const int h = head[r], g = h / G;
-        if (i < 0 || i >= N || h < 0 || h >= Hq) { bad = 2; continue; }
+        if (i < 0 || i >= N || h < 0 || h >= Hq) {
+#pragma omp atomic write
+            bad = 2;
+            continue;
+        }
         const int64_t a = cu[find_segment(cu, n, i)];
         const size_t L = (size_t)(i - a + 1);
         double *S = (double *)malloc(sizeof(double) * L);
         double *P = (double *)malloc(sizeof(double) * L);
         double *dP = (double *)malloc(sizeof(double) * L);
         double *dS = (double *)malloc(sizeof(double) * L);
-        if (!S || !P || !dP || !dS) { bad = 3; free(S); free(P); free(dP); free(dS); continue; }
+        if (!S || !P || !dP || !dS) {
+#pragma omp atomic write
+            bad = 3;
+            free(S); free(P); free(dP); free(dS); continue;
+        }
         out_LSE[r] = softmax_row(Q, K, i, a, h, g, Hq, Hkv, d, scale, S, P);
         double *o = out_O + (size_t)r * d;
         for (int c = 0; c < d; ++c) o[c] = 0.0;
@@ -335,7 +351,11 @@ int oracle_rows_kv(const double *dO, const double *Q, const double *K, const dou
     for (int r = 0; r < m; ++r) {
         const int64_t j = tok[r];
         const int g = kvhead[r];
-        if (j < 0 || j >= N || g < 0 || g >= Hkv) { bad = 2; continue; }
+        if (j < 0 || j >= N || g < 0 || g >= Hkv) {
+#pragma omp atomic write
+            bad = 2;
+            continue;
+        }
         const int s = find_segment(cu, n, j);
         const int64_t a = cu[s], b = cu[s + 1];
         const size_t L = (size_t)(b - a);
@@ -343,7 +363,11 @@ int oracle_rows_kv(const double *dO, const double *Q, const double *K, const dou
         double *P = (double *)malloc(sizeof(double) * L);
         double *dP = (double *)malloc(sizeof(double) * L);
         double *dS = (double *)malloc(sizeof(double) * L);
-        if (!S || !P || !dP || !dS) { bad = 3; free(S); free(P); free(dP); free(dS); continue; }
+        if (!S || !P || !dP || !dS) {
+#pragma omp atomic write
+            bad = 3;
+            free(S); free(P); free(dP); free(dS); continue;
+        }
         double *dk = out_dK + (size_t)r * d, *dv = out_dV + (size_t)r * d;
         for (int c = 0; c < d; ++c) { dk[c] = 0.0; dv[c] = 0.0; }
         for (int h = g * G; h < (g + 1) * G; ++h) {
