@@ -26,8 +26,37 @@ constexpr int kSub = VA_TILE / kBT;  // workgroup tiles per schedule tile
 constexpr int kBS = 64;              // streamed rows per LDS block
 constexpr int kBlk = kBS * kD;       // elements of one swizzled [64][128] LDS block (16 KB)
 constexpr float kLog2e = 1.4426950408889634f;
-VA_TRACE_DECL(g_trace_dq);
-VA_TRACE_DECL(g_trace_dkdv);
+
+// ---- where bf16 operands of the second contraction are carried in two parts ----------------------
+// P and dS enter the matrix instructions as 16-bit values.  With bf16 (8 significant bits) the
+// rounding of the few large entries - rows with a short context, or a peaked softmax - dominates the
+// error of dV, dK and dQ (they are sums over many queries and, with grouped heads, over several
+// heads).  A 32x32 sub-block that holds a probability above kSplitP (a score gradient above kSplitS
+// in magnitude) therefore adds a second pass with the rounding residuals x - bf16(x); elsewhere the
+// residuals are below 2^-9 of those thresholds and are dropped.  fp16 operands (11 bits) need none.
+constexpr float kSplitP = 0.125f;
+constexpr float kSplitS = 1.0f;
+// Queries whose whole context is shorter than this get their dQ corrected for the rounding of O in
+// D = dO . O (see dq_mfma_kernel).
+constexpr int kNearCtx = 64;
+
+template <class E> struct needs_split { static constexpr bool value = false; };
+template <> struct needs_split<Bf16> { static constexpr bool value = true; };
+
+// max |x[v]| over a lane's 16 accumulator values
+__device__ __forceinline__ float abs_max16(const f32x16 &x) {
+  float m = fmaxf(fabsf(x[0]), fabsf(x[1]));
+#pragma unroll
+  for (int v = 2; v < 16; v += 2) m = fmaxf(m, fmaxf(fabsf(x[v]), fabsf(x[v + 1])));
+  return m;
+}
+// Rounding residuals x[v0..v0+7] - float(hi[0..7]) as a second operand.
+template <class E> __device__ __forceinline__ typename E::x8 pack_residual_x8(const f32x16 &x, int v0, typename E::x8 hi) {
+  typename E::x8 r;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) r[e] = (typename E::elem)(x[v0 + e] - (float)hi[e]);
+  return r;
+}
 
 
 // ---------------------------------------------------------------------------------------------
@@ -51,7 +80,6 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   // two stages of {K block, V block}, swizzled
   __shared__ __attribute__((aligned(16))) uint16_t lds[4 * kBlkT];
   static_assert(4 * kBlk * 2 >= 4 * kStageFloatsPerWave * 4, "staging must fit");
-  VA_TRACE_T(tr0);
 
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int l32 = lane & 31, half = lane >> 5;
@@ -166,10 +194,9 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 #pragma unroll
     for (int e = 0; e < 8; ++e) dl = fmaf((float)gf[ks][e], (float)of[e], dl);
   }
-  dl = pair_sum(dl);
-  if (row_ok && half == 0) delta[(size_t)h * N + i_abs] = dl;
+  dl = pair_sum(dl);  // D~: exact up to the rounding of the stored O; refined below
+  float csum = 0.f;   // this lane's share of sum_j dS~_ij
   __syncthreads();  // O has been read: stage 1 may receive the second K/V block
-  VA_TRACE_T(tr1);
 
   // One iteration: start the copy of block jb+1 into the other stage (last read before the previous
   // barrier), consume block jb from (Kb, Vb); the barrier at the end publishes the copied block.
@@ -198,14 +225,31 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
             const int j = jl + acc_row(v, half);
             if (j < ss_i || j > i_abs) p = 0.f;
           }
-          s[v] = p * dp[v];  // dS^T
+          s[v] = p * dp[v];  // dS~^T = P (dP - D~)
+          csum += s[v];
+        }
+        // large score gradients are carried in two bf16 parts: a second pass with the residuals
+        // (wave-uniform choice; rare on long examples, so the K^T fragments are simply read again)
+        const bool split = needs_split<E>::value && __any(abs_max16(s) > kSplitS);
+        const x8 df0 = pack_x8<E>(s, 0), df1 = pack_x8<E>(s, 8);
+        x8 dr0 = df0, dr1 = df1;
+        if (split) {
+          dr0 = pack_residual_x8<E>(s, 0, df0);
+          dr1 = pack_residual_x8<E>(s, 8, df1);
         }
 #pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const x8 df = pack_x8<E>(s, 8 * s2);
+        for (int cb = 0; cb < kCb; ++cb)  // dQ^T += K^T dS^T
+          acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32), df0, acc[cb]);
 #pragma unroll
-          for (int cb = 0; cb < kCb; ++cb)  // dQ^T += K^T dS^T
-            acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + s2 * 16), df, acc[cb]);
+        for (int cb = 0; cb < kCb; ++cb)
+          acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + 16), df1, acc[cb]);
+        if (split) {
+#pragma unroll
+          for (int cb = 0; cb < kCb; ++cb)
+            acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32), dr0, acc[cb]);
+#pragma unroll
+          for (int cb = 0; cb < kCb; ++cb)
+            acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + 16), dr1, acc[cb]);
         }
       }
     }
@@ -217,10 +261,67 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
     if (jb + 1 <= jb_hi) iteration(jb + 1, K1, V1, K0, V0);
   }
 
-  VA_TRACE_T(tr2);
+  // Softmax rows sum to one, so sum_j P_ij (dP_ij - D_i) = 0 for the exact D_i = sum_j P_ij dP_ij.  The
+  // row sum of dS~ is therefore D_i - D~_i, the error that the rounding of the stored O left in
+  // D~ = dO . O: the dK/dV kernel gets D_i itself.
+  const float c_row = pair_sum(csum);
+  if (row_ok && half == 0) delta[(size_t)h * N + i_abs] = dl + c_row;
+  // dQ was accumulated with D~: what is missing is -c_i sum_j P_ij k_j.  It matters where the
+  // probabilities are large, i.e. for queries with a short context (it falls off as 1 / context^2);
+  // waves that hold queries with fewer than kNearCtx keys recompute P on the key sub-blocks from
+  // kNearCtx before their first row on and add K^T (-c P)^T.  Those keys span at most four blocks,
+  // which the stage memory holds at once.
+  const bool near_start = wave_ok && ss_max > iw0 - kNearCtx;  // wave-uniform
+  if (__syncthreads_or(near_start)) {                           // workgroup-uniform; the loop's last barrier freed the stages
+    const int jb_c0 = max(jb_lo, max(t0 - kNearCtx, 0) / kBS);  // jb_hi - jb_c0 <= 3
+#pragma unroll
+    for (int n = 0; n < 4; ++n) {
+      if (jb_c0 + n > jb_hi) break;  // workgroup-uniform
+      const uint32_t off = dma_off + (uint32_t)(jb_c0 + n - jb_lo) * blk_bytes;
+#pragma unroll
+      for (int hf = 0; hf < kHf; ++hf)
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const uint32_t o = dma_ok[hf] ? off + p * p_bytes + hf * 256 : kPastEnd;
+          __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(lds + n * kBlkT + hf * kBlk + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+        }
+    }
+    wait_all_loads();
+    __syncthreads();
+    if (near_start) {
+      const int j_first = max(ss_min, iw0 - kNearCtx);
+      for (int n = 0; n < 4 && jb_c0 + n <= jb_hi; ++n) {
+        const uint16_t *Kb = lds + n * kBlkT;
+#pragma unroll 1
+        for (int sb = 0; sb < 2; ++sb) {
+          const int jl = (jb_c0 + n) * kBS + sb * 32;
+          if (jl > iw1 || jl + 31 < j_first) continue;  // wave-uniform
+          f32x16 sc;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+#pragma unroll
+          for (int ks = 0; ks < kKs; ++ks)
+            sc = mfma32(swz_read_row<E>(Kb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32), qf[ks], sc);
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
+            const int j = jl + acc_row(v, half);
+            const float p = __builtin_amdgcn_exp2f(fmaf(sc[v], scale_log2, -lse2));
+            sc[v] = (j < ss_i || j > i_abs) ? 0.f : -c_row * p;
+          }
+#pragma unroll
+          for (int s2 = 0; s2 < 2; ++s2) {
+            const x8 cf = pack_x8<E>(sc, 8 * s2);
+#pragma unroll
+            for (int cb = 0; cb < kCb; ++cb)
+              acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + s2 * 16), cf, acc[cb]);
+          }
+        }
+      }
+    }
+    __syncthreads();  // the result staging below overlays the blocks just read
+  }
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
   store_transposed_tile<EOut, kCb>(acc, scale, stage, dQ, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h, d);
-  VA_TRACE_STORE(g_trace_dq, tr0, tr1, tr2, jb_hi - jb_lo + 1);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -290,7 +391,6 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   // 1 KB transfers; loading the per-lane fragments straight from HBM (32 rows x 32 B per
   // instruction) took 3 us per workgroup.
   __shared__ __attribute__((aligned(16))) uint16_t kv_own[kKvInStage ? 8 : 2 * kKvSub];
-  VA_TRACE_T(tr0);
 
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int kg = wave % kKg;
@@ -431,12 +531,21 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 #pragma unroll
     for (int ks = 0; ks < kKs; ++ks) x = mfma32(ax[ks], rf[ks], x);  // S - LSE / scale, or dP - D
   };
-  auto second_product = [&](const f32x16 &x, const x8 (&ty)[2][kCb]) {
+  // `split` (wave-uniform): x holds entries large enough for their bf16 rounding to matter; their
+  // residuals go through the matrix pipe as a second operand (see kSplitP / kSplitS)
+  auto second_product = [&](const f32x16 &x, const x8 (&ty)[2][kCb], bool split) {
     const x8 f0 = pack_x8<E>(x, 0), f1 = pack_x8<E>(x, 8);
 #pragma unroll
     for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(ty[0][cb], f0, acc[cb]);  // dV^T += dO^T P, dK^T += Q^T dS
 #pragma unroll
     for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(ty[1][cb], f1, acc[cb]);
+    if (split) {
+      const x8 r0 = pack_residual_x8<E>(x, 0, f0), r1 = pack_residual_x8<E>(x, 8, f1);
+#pragma unroll
+      for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(ty[0][cb], r0, acc[cb]);
+#pragma unroll
+      for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(ty[1][cb], r1, acc[cb]);
+    }
   };
   auto v_step = [&](const uint16_t *__restrict__ cur, int il, int row0, int pw) {
     f32x16 x;
@@ -453,15 +562,17 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
         if (i < j_abs || i >= se_j) x[v] = 0.f;
       }
     }
-    ex[pw * 128] = __builtin_bit_cast(u32x4, pack_x8<E>(x, 0));
-    ex[pw * 128 + 64] = __builtin_bit_cast(u32x4, pack_x8<E>(x, 8));
-    second_product(x, ty);
+    // P goes to the K side as fp16 whatever the inputs' type: probabilities lie in [0, 1], where fp16
+    // keeps 11 significant bits (bf16: 8) down to 6e-5 and absolute 2^-25 below
+    ex[pw * 128] = __builtin_bit_cast(u32x4, pack_x8<F16>(x, 0));
+    ex[pw * 128 + 64] = __builtin_bit_cast(u32x4, pack_x8<F16>(x, 8));
+    second_product(x, ty, needs_split<E>::value && __any(abs_max16(x) > kSplitP));
   };
   auto k_finish = [&](f32x16 &x, const x8 (&ty)[2][kCb], int pr) {  // dS = P (dP - D); dK
-    const x8 p0 = as_x8<E>(ex[pr * 128]), p1 = as_x8<E>(ex[pr * 128 + 64]);
+    const f16x8 p0 = as_x8<F16>(ex[pr * 128]), p1 = as_x8<F16>(ex[pr * 128 + 64]);
 #pragma unroll
     for (int e = 0; e < 8; ++e) { x[e] *= (float)p0[e]; x[8 + e] *= (float)p1[e]; }
-    second_product(x, ty);
+    second_product(x, ty, needs_split<E>::value && __any(abs_max16(x) > kSplitS));
   };
   bool more = false;
   auto begin_block = [&](int it, uint16_t *__restrict__ nxt) {  // returns the block's first query
@@ -520,7 +631,6 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   for (int ks = 0; ks < kKs; ++ks)
     rf[ks] = swz_read_row<E>(kv_tile + ((k_side ? kHf : 0) + (ks >> 3)) * kKvSub, row_lane, ks & 7, kg * 32);
   if (kKvInStage) lds_barrier();  // every wave has its rows before stage 1 receives its first block
-  VA_TRACE_T(tr1);
   if (!k_side) {
     for (int it = 0; it < n_it; it += 2) {  // bounds are workgroup-uniform: barriers stay aligned
       v_iteration(it, S0, S1);
@@ -533,15 +643,12 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
     }
     if (act_b) k_finish(xb, tyb, 1);  // the last sub-block's dK
   }
-
-  VA_TRACE_T(tr2);
   float *stage = (float *)stages + wave * kStageFloatsPerWave;
   const int nrows = wave_ok ? jw1 - jw0 + 1 : 0;
   if (k_side)
     store_transposed_tile<EOut, kCb>(acc, scale, stage, dK, jw0, nrows, hkv, g, d);
   else
     store_transposed_tile<EOut, kCb>(acc, 1.f, stage, dV, jw0, nrows, hkv, g, d);
-  VA_TRACE_STORE(g_trace_dkdv, tr0, tr1, tr2, n_it);
 }
 
 }  // namespace
@@ -562,13 +669,17 @@ static void launch_bwd_t(const uint16_t *g, const uint16_t *q, const uint16_t *k
     if constexpr (kDh <= 128) {
       typedef DkdvShape<kDh, true> Small;
       const unsigned g_small = gkv * (Small::kSubTiles / kSub);
-      // nothing about the lengths is known on the host: both are launched and the device picks
-      dkdv_mfma_kernel<E, EOut, kDh, false><<<g_large, Large::kThreads, 0, stream>>>(
-          g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, 1, N, T, tiles_per_row, hq, hkv, d,
-          scale_log2, scale);
-      dkdv_mfma_kernel<E, EOut, kDh, true><<<g_small, Small::kThreads, 0, stream>>>(
-          g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, 2, N, T, tiles_per_row, hq, hkv, d,
-          scale_log2, scale);
+      // nothing about the lengths is known on the host: both are launched and the device picks,
+      // unless the caller's hint names the shape (select 0 = run unconditionally)
+      const bool only_large = stages & VA_HINT_LONG_EXAMPLES, only_small = stages & VA_HINT_SHORT_EXAMPLES;
+      if (!only_small)
+        dkdv_mfma_kernel<E, EOut, kDh, false><<<g_large, Large::kThreads, 0, stream>>>(
+            g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, only_large ? 0 : 1, N, T,
+            tiles_per_row, hq, hkv, d, scale_log2, scale);
+      if (!only_large)
+        dkdv_mfma_kernel<E, EOut, kDh, true><<<g_small, Small::kThreads, 0, stream>>>(
+            g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, only_small ? 0 : 2, N, T,
+            tiles_per_row, hq, hkv, d, scale_log2, scale);
     } else {
       dkdv_mfma_kernel<E, EOut, kDh, false><<<g_large, Large::kThreads, 0, stream>>>(
           g, q, k, v, LSE, delta, dK, dV, seg.seg_end, seg.kv_tile_order, seg.meta, 0, N, T, tiles_per_row, hq, hkv, d,
@@ -614,12 +725,5 @@ hipError_t launch_mfma_bwd(const void *dO, const void *Q, const void *K, const v
   return hipGetLastError();
 }
 
-#ifdef VA_TRACE
-hipError_t trace_read_bwd(int which, void *host, size_t bytes) {
-  if (bytes > sizeof(g_trace_dq)) bytes = sizeof(g_trace_dq);
-  return which == 0 ? hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_dq), bytes)
-                    : hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_dkdv), bytes);
-}
-#endif
 
 }  // namespace va
