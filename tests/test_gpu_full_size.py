@@ -1,10 +1,14 @@
 """Parity at the full sizes of the benchmark configurations, through the same calls and launch
 configuration bench.py times.
 
-Config 2 (the benchmarked workload) is compared element by element against the full oracle.
-Configs 3-5 are compared on sampled output rows the oracle computes one by one (forward rows,
-dQ rows, dK/dV rows), plus properties that hold at any size.
+Every configuration (2-5) is compared element by element, whole tensors, against the full oracle:
+once with gradients emitted in fp32 (max-abs 2e-2, relative L2 5e-3) and once with gradients stored
+in bf16, the type bench.py times (2e-2 + 2^-8 |ref| per element for the store's own rounding, the same
+relative L2; and within one bf16 step of the fp32 result).  Outputs start as NaN, so an element
+that no workgroup wrote fails.  The sampled-row test below stays as a fast pre-check.
 """
+import time
+
 import numpy as np
 import pytest
 import torch
@@ -12,19 +16,40 @@ import torch
 from oracle import oracle
 from paper_2407_09105_amd import binding, workloads as wl
 from tests.gpu_util import (BF16_MAX_ABS, BF16_REL_L2, DEV, assert_close, assert_seg_equal, max_abs, rel_l2,
-                            run_gpu, run_oracle, to_dev)
+                            run_gpu, run_oracle, run_oracle_in_steps, to_dev)
 
 pytestmark = pytest.mark.gpu
 
 
-def test_config2_full_elementwise():
-    w = wl.make_workload(2)
-    print("config 2:", w.stats, flush=True)
-    got = run_gpu(w, grad_dtype=torch.float32)
-    ref = run_oracle(w)
+@pytest.fixture(scope="module", params=[2, 3, 4, 5])
+def full_case(request):
+    """(workload, oracle results) of one configuration; the oracle runs once per configuration
+    (config 5 is 6 TFLOP of fp64 work: minutes on the host cores)."""
+    w = wl.make_workload(request.param)
+    print(f"config {request.param}:", w.stats, "- running the oracle in full", flush=True)
+    t0 = time.time()
+    ref = run_oracle_in_steps(w)
+    print(f"   oracle: {time.time() - t0:.0f} s on {oracle.num_threads()} threads", flush=True)
+    return w, ref
+
+
+@pytest.mark.timeout(1500)
+@pytest.mark.parametrize("grads", ["f32", "bf16"])
+def test_whole_tensors_against_the_oracle(full_case, grads):
+    w, ref = full_case
+    gdt = torch.float32 if grads == "f32" else torch.bfloat16
+    got = run_gpu(w, grad_dtype=gdt, nan_fill=True)
     assert_seg_equal(got["seg"], ref["seg"])
-    errs = assert_close(got, ref, "bf16")
-    print("   errors (max-abs, rel-L2):", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in errs.items()}, flush=True)
+    for key in ("O", "LSE", "dQ", "dK", "dV"):
+        assert np.isfinite(got[key]).all(), key          # every element was written
+    print(f"   config {w.cfg.cfg}, gradients in {grads}:", flush=True)
+    assert_close(got, ref, "bf16", bf16_stored=("dQ", "dK", "dV") if grads == "bf16" else ())
+    if grads == "bf16":
+        # the same arithmetic with a 16-bit store: one bf16 step from the fp32 result at most
+        g32 = run_gpu(w, grad_dtype=torch.float32)
+        for key in ("dQ", "dK", "dV"):
+            step = np.maximum(np.abs(g32[key]), 2.0 ** -126) * 2.0 ** -7
+            assert (np.abs(got[key] - g32[key]) <= step).all(), key
 
 
 def _sample_kv(rng, cu, n_cheap, n_costly, cheap_cap=5e5, costly_cap=1e7):
@@ -181,13 +206,10 @@ def test_byte_offsets_up_to_the_32bit_limit(T, Hq, Hkv, d):
     tki = torch.from_numpy(tk.astype(np.int64)).to(DEV)
     hki = kh[torch.from_numpy(hk.astype(np.int64)).to(DEV)]
     got["dK"], got["dV"] = f(dk[tki, hki]), f(dv[tki, hki])
-    # dK / dV of the first keys sum up to 3800 queries x G heads and reach several units: the error of the bf16
-    # P and dS operands grows with the row's size, so the element-wise bar is taken relative to the row's rms
-    # where that exceeds 1, plus the rounding of the bf16 store; the relative-L2 bar is the usual one
+    # gradients are stored in bf16 here: the stated bar plus the rounding of the store itself
     for key in got:
         assert rel_l2(got[key], ref[key]) <= BF16_REL_L2, key
-        rms = np.sqrt((ref[key] ** 2).mean(axis=1, keepdims=True))
-        bound = BF16_MAX_ABS * np.maximum(1.0, rms) + (np.abs(ref[key]) / 256.0 if key != "O" else 0.0)
+        bound = BF16_MAX_ABS + (np.abs(ref[key]) / 256.0 if key != "O" else 0.0)
         assert (np.abs(got[key] - ref[key]) <= bound).all(), (key, max_abs(got[key], ref[key]))
     assert max_abs(f(lse[hi, ti]), LSEr) <= 1e-3
     for t in (o, lse, dq, dk, dv):
