@@ -127,7 +127,8 @@ va_status va_collate_padding_free(const void *ids_padded, const void *labels_pad
  *   position_ids  : device, [n_tokens] of `it` (the flattened [rows, tokens_per_row] ids).
  *   theta_base    : <= 0 means 10000.
  *   inverse       : non-zero rotates by -a (the transpose): d(loss)/dx from d(loss)/dy.
- * Angles are formed and range-reduced in fp64, products in fp32; bf16 results are rounded to nearest even.
+ * Angles are formed and range-reduced in fp64, products in fp32; bf16 / fp16 results are rounded to
+ * nearest even.  All three element types are accepted.
  */
 va_status va_rope_apply(const void *x, void *y, va_dtype dt, const void *position_ids, va_itype it,
                         int32_t n_tokens, int32_t heads, int32_t d, float theta_base, int inverse,
@@ -178,47 +179,32 @@ va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const
  * `stages` is an OR of the flags below.
  *   VA_STAGE_D    D = rowsum(dO * O) into `workspace`.
  *   VA_STAGE_DQ   dQ.  The plain kernels read D from `workspace`; the MFMA kernel forms D for its
- *                 own rows and (re)writes `workspace` with it.
+ *                 own rows and (re)writes `workspace` with it - refined by the row sums of dS, which
+ *                 take out the rounding of the stored O (so dK/dV are most accurate after this stage).
  *   VA_STAGE_DKDV dK, dV; reads the D that an earlier VA_STAGE_D or VA_STAGE_DQ left in `workspace`.
  * Within one call the order is D (skipped when the MFMA dQ kernel makes it redundant), dQ, dK/dV;
  * all three flags give exactly va_varlen_attn_bwd.
- * Arguments, validation and errors as va_varlen_attn_bwd; stages == 0 or unknown bits: VA_ERR_UNSUPPORTED.
+ * The MFMA dK/dV kernel has two workgroup shapes (head_dim <= 128): 128-key tiles for batches of long
+ * examples, 64-key tiles otherwise.  By default both are enqueued and the device picks by the batch's
+ * mean example length (the host never sees the lengths); the other's workgroups leave at once.  A
+ * caller that knows its lengths can add ONE of
+ *   VA_HINT_LONG_EXAMPLES   mean example length >= 1024 tokens: only the 128-key shape is enqueued
+ *   VA_HINT_SHORT_EXAMPLES  otherwise: only the 64-key shape
+ * Either shape computes every result whatever the lengths; a wrong hint costs speed only.
+ * Arguments, validation and errors as va_varlen_attn_bwd; no stage bit, both hints or unknown bits:
+ * VA_ERR_UNSUPPORTED.
  */
 #define VA_STAGE_D 1u
 #define VA_STAGE_DKDV 2u
 #define VA_STAGE_DQ 4u
+#define VA_HINT_LONG_EXAMPLES 8u
+#define VA_HINT_SHORT_EXAMPLES 16u
 va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K, const void *V,
                                     const void *O, const float *LSE, void *dQ, void *dK, void *dV,
                                     va_dtype grad_dt, const va_segments *seg, int32_t rows,
                                     int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
                                     va_dtype dt, float softmax_scale, void *workspace,
                                     size_t workspace_bytes, void *stream, uint32_t stages);
-
-/*
- * Measurement aid (no part of the method): enqueue a kernel that issues nothing but bf16
- * 32x32x16 matrix instructions on every SIMD, `iters` (1 .. 2^24) rounds of 16 per wave.  The caller
- * times it with events on `stream`; *flops (host, may be NULL) receives the floating-point
- * operations the launch performs.  flops / time is the matrix rate this GPU sustains, reported by
- * the benchmark beside the published peak.  sink: device, >= 64 floats, normally left untouched.
- */
-va_status va_probe_mfma(float *sink, int32_t iters, double *flops /* host, out */, void *stream);
-
-/*
- * Measurement aid (no part of the method): the same matrix instructions in the company they keep
- * in the attention kernels.  operands: device, 64 KB of 16-bit values with the bit patterns of real
- * inputs (e.g. N(0,1) rounded to bf16), which the kernel stages in LDS and multiplies (the rate a
- * power-limited GPU sustains depends on how many operand bits toggle).  Per 16 matrix instructions
- * a wave also issues `lds_reads` 1 KB fragment reads from LDS and `valu_groups` groups of
- * {fma, exp2, max, add}, all independent of the matrix instructions, 2 waves per SIMD.  Supported
- * (lds_reads, valu_groups): (0,0), (8,0), (16,0), (16,24) - the forward kernel's mix -, (16,12) and
- * (8,16); others return VA_ERR_UNSUPPORTED.  flops / time (caller's events on `stream`) bounds what
- * a kernel with that instruction mix can reach on this GPU.  clocks (device, 2 x uint64, may be NULL)
- * receives the shader-clock ticks and the 100 MHz wall-clock ticks of one wave's loop: their ratio
- * is the clock the GPU held under that load.  sink: device, >= 64 floats, normally left untouched.
- */
-va_status va_probe_mix(const void *operands, int32_t lds_reads, int32_t valu_groups, float *sink,
-                       uint64_t *clocks /* device, out */, int32_t iters, double *flops /* host, out */,
-                       void *stream);
 
 /* Static string for a status code. */
 const char *va_status_string(va_status s);

@@ -21,11 +21,12 @@ VA_F32, VA_BF16, VA_F16 = 0, 1, 2
 VA_I32, VA_I64 = 0, 1
 VA_TILE = 256
 STAGE_D, STAGE_DKDV, STAGE_DQ = 1, 2, 4
+HINT_LONG_EXAMPLES, HINT_SHORT_EXAMPLES = 8, 16
 
 EXPORTS = (
     "va_plan_bytes", "va_segments_bind", "va_pack_to_cu_seqlens", "va_attn_workspace_bytes",
     "va_varlen_attn_fwd", "va_varlen_attn_bwd", "va_varlen_attn_bwd_stages", "va_collate_padding_free",
-    "va_rope_apply", "va_probe_mfma", "va_probe_mix", "va_status_string", "va_version",
+    "va_rope_apply", "va_status_string", "va_version",
 )
 
 
@@ -70,11 +71,6 @@ def lib() -> C.CDLL:
     L.va_rope_apply.restype = C.c_int
     L.va_rope_apply.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_int32, C.c_int32,
                                 C.c_int32, C.c_float, C.c_int, C.c_void_p]
-    L.va_probe_mfma.restype = C.c_int
-    L.va_probe_mfma.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_double), C.c_void_p]
-    L.va_probe_mix.restype = C.c_int
-    L.va_probe_mix.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
-                               C.POINTER(C.c_double), C.c_void_p]
     L.va_status_string.restype = C.c_char_p
     L.va_status_string.argtypes = [C.c_int]
     L.va_version.restype = C.c_char_p
@@ -207,6 +203,12 @@ def collate_padding_free(ids_padded: torch.Tensor, lengths: torch.Tensor, n_out:
         out = {k: torch.empty((1, n_out), dtype=ids_padded.dtype, device=dev)
                for k in ("input_ids", "labels", "position_ids")}
         out["example_offsets"] = torch.empty(n + 1, dtype=torch.int32, device=dev)
+    else:
+        for key in ("input_ids", "labels", "position_ids"):
+            if out[key].numel() != n_out:
+                raise ValueError(f"out[{key!r}] must hold n_out = {n_out} elements")
+            _out_like(f"out[{key!r}]", out[key], out[key].shape, ids_padded.dtype, dev)
+        _out_like("out['example_offsets']", out["example_offsets"], (n + 1,), torch.int32, dev)
     _check("va_collate_padding_free", lib().va_collate_padding_free(
         ids_padded.data_ptr() if n else None, None if labels_padded is None else labels_padded.data_ptr(), it,
         lengths.data_ptr() if n else None, n, Lp, n_out, int(pad_id), out["input_ids"].data_ptr(),
@@ -216,7 +218,7 @@ def collate_padding_free(ids_padded: torch.Tensor, lengths: torch.Tensor, n_out:
 
 def rope_apply(x: torch.Tensor, position_ids: torch.Tensor, theta_base: float = 10000.0, inverse: bool = False,
                out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Rotary embedding of x [N, H, d] (float32 or bfloat16) at position_ids (N entries, int32/int64).
+    """Rotary embedding of x [N, H, d] (float32, bfloat16 or float16) at position_ids (N entries, int32/int64).
     out may be x (in place).  Enqueues one kernel."""
     _need_cuda(x, position_ids)
     if x.dim() != 3 or position_ids.numel() != x.shape[0]:
@@ -234,32 +236,13 @@ def rope_apply(x: torch.Tensor, position_ids: torch.Tensor, theta_base: float = 
     return y
 
 
-def probe_mfma(sink: torch.Tensor, iters: int) -> float:
-    """Enqueue the matrix-instruction-only kernel; returns the FLOPs it performs (time it with events)."""
-    _need_cuda(sink)
-    if sink.dtype != torch.float32 or sink.numel() < 64:
-        raise ValueError("sink must hold at least 64 float32")
-    fl = C.c_double(0.0)
-    _check("va_probe_mfma", lib().va_probe_mfma(sink.data_ptr(), int(iters), C.byref(fl), _stream()))
-    return fl.value
-
-
-def probe_mix(operands: torch.Tensor, lds_reads: int, valu_groups: int, sink: torch.Tensor,
-              clocks: Optional[torch.Tensor], iters: int) -> float:
-    """Enqueue the matrix + LDS + vector-ALU mix kernel; returns its matrix FLOPs (time it with events).
-    operands: >= 64 KB of 16-bit values on the device; clocks: 2 x int64 on the device or None."""
-    _need_cuda(operands, sink)
-    if operands.numel() * operands.element_size() < 65536:
-        raise ValueError("operands must hold at least 64 KB")
-    if sink.dtype != torch.float32 or sink.numel() < 64:
-        raise ValueError("sink must hold at least 64 float32")
-    if clocks is not None and (clocks.dtype != torch.int64 or clocks.numel() < 2 or not clocks.is_cuda):
-        raise ValueError("clocks must hold 2 int64 on the device")
-    fl = C.c_double(0.0)
-    _check("va_probe_mix", lib().va_probe_mix(operands.data_ptr(), int(lds_reads), int(valu_groups), sink.data_ptr(),
-                                              clocks.data_ptr() if clocks is not None else None, int(iters),
-                                              C.byref(fl), _stream()))
-    return fl.value
+def _out_like(name: str, t: torch.Tensor, shape, dtype, device):
+    """A caller-supplied output buffer must be exactly what the library will write: it only gets the pointer."""
+    _need_cuda(t)
+    if tuple(t.shape) != tuple(shape) or t.dtype != dtype or t.device != device:
+        raise ValueError(f"{name} must be a contiguous {dtype} tensor of shape {tuple(shape)} on {device}, "
+                         f"got {t.dtype} {tuple(t.shape)} on {t.device}")
+    return t
 
 
 def _shapes(q, k, v, seg):
@@ -278,8 +261,9 @@ def varlen_attn_fwd(q, k, v, seg: Segments, softmax_scale: float = 0.0, out=None
     N, hq, hkv, d = _shapes(q, k, v, seg)
     if not (q.dtype == k.dtype == v.dtype):
         raise TypeError("Q, K, V must share a dtype")
-    o = torch.empty_like(q) if out is None else out
-    lse = torch.empty((hq, N), dtype=torch.float32, device=q.device) if lse is None else lse
+    o = torch.empty_like(q) if out is None else _out_like("out", out, q.shape, q.dtype, q.device)
+    lse = (torch.empty((hq, N), dtype=torch.float32, device=q.device) if lse is None
+           else _out_like("lse", lse, (hq, N), torch.float32, q.device))
     _check("va_varlen_attn_fwd", lib().va_varlen_attn_fwd(
         q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(), C.byref(seg.c),
         seg.rows, seg.tokens_per_row, hq, hkv, d, _dt(q), float(softmax_scale), None, 0, _stream()))
@@ -296,18 +280,27 @@ def varlen_attn_bwd(do, q, k, v, o, lse, seg: Segments, softmax_scale: float = 0
                     grad_dtype: Optional[torch.dtype] = None, dq=None, dk=None, dv=None, workspace=None,
                     stages: Optional[int] = None):
     """-> dQ [N, Hq, d], dK, dV [N, Hkv, d] in grad_dtype (default: dtype of q).
-    `stages` (an OR of STAGE_D, STAGE_DKDV, STAGE_DQ) runs only those kernels of the backward."""
+    `stages` (an OR of STAGE_D, STAGE_DKDV, STAGE_DQ, optionally with HINT_LONG_EXAMPLES or
+    HINT_SHORT_EXAMPLES) runs only those kernels of the backward."""
     _need_cuda(do, q, k, v, o, lse)
     N, hq, hkv, d = _shapes(q, k, v, seg)
     if not (q.dtype == k.dtype == v.dtype == o.dtype == do.dtype):
         raise TypeError("dO, Q, K, V, O must share a dtype")
     if lse.dtype != torch.float32 or tuple(lse.shape) != (hq, N):
         raise ValueError("LSE must be float32 [Hq, N]")
-    gdt = q.dtype if grad_dtype is None else grad_dtype
-    dq = torch.empty(q.shape, dtype=gdt, device=q.device) if dq is None else dq
-    dk = torch.empty(k.shape, dtype=gdt, device=q.device) if dk is None else dk
-    dv = torch.empty(v.shape, dtype=gdt, device=q.device) if dv is None else dv
-    ws = bwd_workspace(q, k) if workspace is None else workspace
+    given = [t for t in (dq, dk, dv) if t is not None]
+    gdt = grad_dtype if grad_dtype is not None else (given[0].dtype if given else q.dtype)
+    dq = torch.empty(q.shape, dtype=gdt, device=q.device) if dq is None else _out_like("dq", dq, q.shape, gdt, q.device)
+    dk = torch.empty(k.shape, dtype=gdt, device=q.device) if dk is None else _out_like("dk", dk, k.shape, gdt, q.device)
+    dv = torch.empty(v.shape, dtype=gdt, device=q.device) if dv is None else _out_like("dv", dv, v.shape, gdt, q.device)
+    if workspace is None:
+        ws = bwd_workspace(q, k)
+    else:
+        ws = workspace
+        _need_cuda(ws)
+        need = lib().va_attn_workspace_bytes(N, hq, hkv, d, 1)
+        if ws.dtype != torch.float32 or ws.numel() * 4 < need or ws.device != q.device:
+            raise ValueError(f"workspace must be a contiguous float32 tensor of at least {need} bytes on {q.device}")
     args = [do.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
             dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _dt(dq), C.byref(seg.c), seg.rows, seg.tokens_per_row,
             hq, hkv, d, _dt(q), float(softmax_scale), ws.data_ptr(), ws.numel() * 4, _stream()]
@@ -316,3 +309,4 @@ def varlen_attn_bwd(do, q, k, v, o, lse, seg: Segments, softmax_scale: float = 0
     else:
         _check("va_varlen_attn_bwd_stages", lib().va_varlen_attn_bwd_stages(*args, int(stages)))
     return dq, dk, dv
+

@@ -1,4 +1,5 @@
-"""Build libvarlen_attn.so (HIP, gfx950) in-tree with hipcc."""
+"""Build the HIP libraries (gfx950) in-tree with hipcc: libvarlen_attn.so, the attention library
+(csrc/*.hip), and libva_probes.so, the benchmark's measurement aids (probes/*.hip)."""
 import glob
 import os
 import subprocess
@@ -7,7 +8,9 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
+PROBES = os.path.join(HERE, "probes")
 LIB = os.path.join(HERE, "libvarlen_attn.so")
+PROBES_LIB = os.path.join(HERE, "libva_probes.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 FLAGS = [
@@ -16,24 +19,27 @@ FLAGS = [
     "-I" + os.path.join(ROOT, "include"), "-I" + CSRC,
 ]
 
+TARGETS = ((LIB, CSRC), (PROBES_LIB, PROBES))
 
-def sources():
-    return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+
+def sources(src_dir=CSRC):
+    return sorted(glob.glob(os.path.join(src_dir, "*.hip")))
 
 
 def build(verbose: bool = False, extra_flags=()) -> str:
-    """Compile every .hip source and link the shared library; always recompiles."""
+    """Compile every .hip source and link both shared libraries; always recompiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     os.makedirs(OBJ_DIR, exist_ok=True)
     procs = []
-    objs = []
-    for src in sources():
-        obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
-        objs.append(obj)
-        cmd = [hipcc, *FLAGS, *extra_flags, "-c", src, "-o", obj]
-        if verbose:
-            print(" ".join(cmd), flush=True)
-        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+    objs = {lib: [] for lib, _ in TARGETS}
+    for lib, src_dir in TARGETS:
+        for src in sources(src_dir):
+            obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+            objs[lib].append(obj)
+            cmd = [hipcc, *FLAGS, "-I" + src_dir, *extra_flags, "-c", src, "-o", obj]
+            if verbose:
+                print(" ".join(cmd), flush=True)
+            procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     failed = False
     for src, p in procs:
         out, _ = p.communicate()
@@ -46,8 +52,8 @@ def build(verbose: bool = False, extra_flags=()) -> str:
             print(out)
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
-    subprocess.check_call(cmd)
+    for lib, _ in TARGETS:
+        subprocess.check_call([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs[lib], "-o", lib])
     return LIB
 
 

@@ -63,13 +63,6 @@ va_status check_common(const va_segments *seg, int32_t rows, int32_t T, int32_t 
 
 }  // namespace
 
-#ifdef VA_TRACE
-namespace va {
-hipError_t trace_read_fwd(void *host, size_t bytes);
-hipError_t trace_read_bwd(int which, void *host, size_t bytes);
-}
-#endif
-
 extern "C" {
 
 size_t va_plan_bytes(int32_t rows, int32_t tokens_per_row) {
@@ -128,33 +121,13 @@ va_status va_rope_apply(const void *x, void *y, va_dtype dt, const void *positio
                         int32_t n_tokens, int32_t heads, int32_t d, float theta_base, int inverse,
                         void *stream) {
   if (n_tokens < 0 || heads <= 0 || d <= 0 || (d & 1)) return VA_ERR_SHAPE;
-  if (dt != VA_F32 && dt != VA_BF16) return VA_ERR_UNSUPPORTED;
+  if (dt != VA_F32 && dt != VA_BF16 && dt != VA_F16) return VA_ERR_UNSUPPORTED;
   if (it != VA_I32 && it != VA_I64) return VA_ERR_UNSUPPORTED;
   if (d > 256) return VA_ERR_UNSUPPORTED;
   if (n_tokens > 0 && (!x || !y || !position_ids)) return VA_ERR_NULL;
   const double base = theta_base > 0.f ? (double)theta_base : 10000.0;
   hipError_t e = va::launch_rope(x, y, dt, position_ids, it, n_tokens, heads, d, base, inverse != 0,
                                  (hipStream_t)stream);
-  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
-}
-
-va_status va_probe_mfma(float *sink, int32_t iters, double *flops, void *stream) {
-  if (!sink) return VA_ERR_NULL;
-  if (iters <= 0 || iters > (1 << 24)) return VA_ERR_SHAPE;
-  hipError_t e = va::launch_mfma_probe(sink, iters, flops, (hipStream_t)stream);
-  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
-}
-
-va_status va_probe_mix(const void *operands, int32_t lds_reads, int32_t valu_groups, float *sink,
-                       uint64_t *clocks, int32_t iters, double *flops, void *stream) {
-  if (!operands || !sink) return VA_ERR_NULL;
-  if (iters <= 0 || iters > (1 << 24)) return VA_ERR_SHAPE;
-  const bool known = (valu_groups == 0 && (lds_reads == 0 || lds_reads == 8 || lds_reads == 16)) ||
-                     (lds_reads == 16 && (valu_groups == 24 || valu_groups == 12)) ||
-                     (lds_reads == 8 && valu_groups == 16);
-  if (!known) return VA_ERR_UNSUPPORTED;
-  hipError_t e = va::launch_mix_probe(operands, lds_reads, valu_groups, sink, (unsigned long long *)clocks, iters,
-                                      flops, (hipStream_t)stream);
   return e == hipSuccess ? VA_OK : VA_ERR_HIP;
 }
 
@@ -183,19 +156,32 @@ va_status va_varlen_attn_fwd(const void *Q, const void *K, const void *V, void *
   return e == hipSuccess ? VA_OK : VA_ERR_HIP;
 }
 
-va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K, const void *V,
-                                    const void *O, const float *LSE, void *dQ, void *dK, void *dV,
-                                    va_dtype grad_dt, const va_segments *seg, int32_t rows,
-                                    int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
-                                    va_dtype dt, float softmax_scale, void *workspace,
-                                    size_t workspace_bytes, void *stream, uint32_t stages) {
+namespace {
+// Host-side validation of a backward call: everything except the workspace.
+va_status check_bwd(const void *dO, const void *Q, const void *K, const void *V, const void *O, const float *LSE,
+                    void *dQ, void *dK, void *dV, va_dtype grad_dt, const va_segments *seg, int32_t rows,
+                    int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d, va_dtype dt, uint32_t stages) {
   if (!dO || !Q || !K || !V || !O || !LSE || !dQ || !dK || !dV) return VA_ERR_NULL;
   va_status s = check_common(seg, rows, tokens_per_row, hq, hkv, d, dt);
   if (s != VA_OK) return s;
   // gradients come out in fp32 or in the inputs' own 16-bit type (fp32 inputs: fp32 or bf16)
   if (grad_dt != VA_F32 && !(grad_dt == VA_BF16 && dt != VA_F16) && !(grad_dt == VA_F16 && dt == VA_F16))
     return VA_ERR_UNSUPPORTED;
-  if (stages == 0 || (stages & ~(VA_STAGE_D | VA_STAGE_DKDV | VA_STAGE_DQ))) return VA_ERR_UNSUPPORTED;
+  constexpr uint32_t kStages = VA_STAGE_D | VA_STAGE_DKDV | VA_STAGE_DQ;
+  constexpr uint32_t kHints = VA_HINT_LONG_EXAMPLES | VA_HINT_SHORT_EXAMPLES;
+  if ((stages & kStages) == 0 || (stages & ~(kStages | kHints)) || (stages & kHints) == kHints) return VA_ERR_UNSUPPORTED;
+  return VA_OK;
+}
+}  // namespace
+
+va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K, const void *V,
+                                    const void *O, const float *LSE, void *dQ, void *dK, void *dV,
+                                    va_dtype grad_dt, const va_segments *seg, int32_t rows,
+                                    int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
+                                    va_dtype dt, float softmax_scale, void *workspace,
+                                    size_t workspace_bytes, void *stream, uint32_t stages) {
+  va_status s = check_bwd(dO, Q, K, V, O, LSE, dQ, dK, dV, grad_dt, seg, rows, tokens_per_row, hq, hkv, d, dt, stages);
+  if (s != VA_OK) return s;
   const int N = rows * tokens_per_row;
   const size_t need = va_attn_workspace_bytes(N, hq, hkv, d, 1);
   if (!workspace) return VA_ERR_NULL;
@@ -204,6 +190,7 @@ va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K
   float *delta = (float *)workspace;
   hipStream_t st = (hipStream_t)stream;
   hipError_t e = hipSuccess;
+  const unsigned hints = stages & (VA_HINT_LONG_EXAMPLES | VA_HINT_SHORT_EXAMPLES);
   const unsigned mfma_stages = ((use_mfma(dt, d, kMfmaDqMaxD) ? VA_STAGE_DQ : 0u) |
                                 (use_mfma(dt, d, kMfmaDkdvMaxD) ? VA_STAGE_DKDV : 0u)) & stages;
   const unsigned plain_stages = stages & (VA_STAGE_DKDV | VA_STAGE_DQ) & ~mfma_stages;
@@ -212,7 +199,7 @@ va_status va_varlen_attn_bwd_stages(const void *dO, const void *Q, const void *K
   if (e != hipSuccess) return VA_ERR_HIP;
   if (mfma_stages)
     e = va::launch_mfma_bwd(dO, Q, K, V, O, LSE, delta, dQ, dK, dV, grad_dt, *seg, rows, tokens_per_row, hq, hkv,
-                            d, dt, scale, st, mfma_stages);
+                            d, dt, scale, st, mfma_stages | hints);
   if (e != hipSuccess) return VA_ERR_HIP;
   if (plain_stages)
     e = va::launch_generic_bwd(dO, Q, K, V, LSE, delta, dQ, dK, dV, grad_dt, *seg, N, hq, hkv, d, dt, scale, st,
@@ -245,14 +232,5 @@ const char *va_status_string(va_status s) {
 
 const char *va_version(void) { return "varlen_attn 0.1 (gfx950)"; }
 
-#ifdef VA_TRACE
-// Timeline build only (-DVA_TRACE): copies the per-workgroup records of the last launch of the
-// forward (0), dQ (1) or dK/dV (2) kernel to the host; synchronises the device.
-int va_trace_read(int kernel, void *host, size_t bytes) {
-  if (hipDeviceSynchronize() != hipSuccess) return VA_ERR_HIP;
-  const hipError_t e = kernel == 0 ? va::trace_read_fwd(host, bytes) : va::trace_read_bwd(kernel - 1, host, bytes);
-  return e == hipSuccess ? VA_OK : VA_ERR_HIP;
-}
-#endif
 
 }  // extern "C"

@@ -32,7 +32,6 @@ constexpr int kBN = 32;           // key rows per LDS block
 constexpr int kBlk = kBN * kD;    // elements of one swizzled [32][128] LDS block (8 KB)
 constexpr int kStagingElems = 4 * kStageFloatsPerWave * 2;  // the result staging of four waves, in 16-bit units
 constexpr float kLazyLog2 = 8.f;  // keep a stale row maximum while probabilities stay <= 2^8
-VA_TRACE_DECL(g_trace_fwd);
 
 // E: element type (Bf16 / F16); kDh: head_dim rounded up to 64, 96, 128 or 256 (k-steps and column
 // blocks the kernel is unrolled for); d: the tensors' head_dim (a multiple of 8, <= kDh).  With
@@ -50,8 +49,6 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   typedef typename E::x8 x8;
   // stage 0 = {K, V} at lds[0 .. 2 kBlkT), stage 1 = {K, V} at lds[2 kBlkT .. 4 kBlkT)
   __shared__ __attribute__((aligned(16))) uint16_t lds[4 * kBlkT > kStagingElems ? 4 * kBlkT : kStagingElems];
-
-  VA_TRACE_T(tr0);
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int l32 = lane & 31, half = lane >> 5;
   const uint32_t row_lane = swz_row_lane_off(lane);
@@ -193,20 +190,17 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
   copy_block(K0, V0, jb_lo);
   wait_all_loads();  // Q fragments too: inside the loop only block copies are in flight
   __syncthreads();
-  VA_TRACE_T(tr1);
   for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
     iteration(jb, K0, V0, K1, V1);
     if (jb + 1 <= jb_hi) iteration(jb + 1, K1, V1, K0, V0);
   }
 
   // ---- epilogue: normalise, stage O through LDS, coalesced stores ----
-  VA_TRACE_T(tr2);
   const float l_tot = pair_sum(l_run);
   const float inv = row_ok ? 1.f / l_tot : 0.f;
   if (row_ok && half == 0) LSE[(size_t)h * N + i_abs] = m_ref * scale + __logf(l_tot);
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
   store_transposed_tile<E, kCb>(o_acc, inv, stage, O, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h, d);
-  VA_TRACE_STORE(g_trace_fwd, tr0, tr1, tr2, jb_hi - jb_lo + 1);
 }
 
 }  // namespace
@@ -241,10 +235,5 @@ hipError_t launch_mfma_fwd(const void *Q, const void *K, const void *V, void *O,
   return hipGetLastError();
 }
 
-#ifdef VA_TRACE
-hipError_t trace_read_fwd(void *host, size_t bytes) {
-  return hipMemcpyFromSymbol(host, HIP_SYMBOL(g_trace_fwd), bytes < sizeof(g_trace_fwd) ? bytes : sizeof(g_trace_fwd));
-}
-#endif
 
 }  // namespace va

@@ -25,11 +25,6 @@ hipError_t launch_collate(const void *ids, const void *labels_in, va_itype it, c
 hipError_t launch_rope(const void *x, void *y, va_dtype dt, const void *pos, va_itype it, long long N,
                        int H, int d, double base, int inverse, hipStream_t stream);
 
-// va_probe.hip
-hipError_t launch_mfma_probe(float *sink, int iters, double *flops, hipStream_t stream);
-hipError_t launch_mix_probe(const void *operands, int lds_reads, int valu_groups, float *sink,
-                            unsigned long long *clocks, int iters, double *flops, hipStream_t stream);
-
 // va_generic.hip : plain fp32-arithmetic kernels, any head_dim <= 256
 hipError_t launch_generic_fwd(const void *Q, const void *K, const void *V, void *O, float *LSE,
                               const va_segments &seg, int N, int hq, int hkv, int d, va_dtype dt,

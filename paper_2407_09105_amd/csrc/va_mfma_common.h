@@ -279,33 +279,4 @@ __device__ __forceinline__ void store_transposed_tile(const f32x16 (&acc)[kCb], 
 }
 
 
-// ---- optional per-workgroup timeline (build with -DVA_TRACE; not part of the normal library) ----
-// Each workgroup of an MFMA kernel records the constant-rate wall clock (100 MHz) at its start, at the
-// end of its prologue, at the end of its loop and at its end, the compute unit it ran on and its trip count, into a
-// file-scope device array that va_trace_read_* copies to the host.  Used to see how a launch fills
-// the chip: tails, imbalance, how long a workgroup's fixed parts take next to its loop.
-#ifdef VA_TRACE
-struct TraceRec { unsigned long long t0, t1, t2, t3, info, pad[3]; };
-constexpr int kTraceMax = 32768;
-__device__ __forceinline__ unsigned long long trace_where(int trips) {
-  const unsigned hw = __builtin_amdgcn_s_getreg((31 << 11) | 4);    // HW_ID: cu [11:8], sh [12], se [15:13]
-  const unsigned xcc = __builtin_amdgcn_s_getreg((3 << 11) | 20);   // XCC_ID [3:0]
-  const unsigned cu = (xcc & 15u) << 8 | ((hw >> 13) & 7u) << 5 | ((hw >> 12) & 1u) << 4 | ((hw >> 8) & 15u);
-  return ((unsigned long long)cu << 32) | (unsigned)trips;
-}
-#define VA_TRACE_DECL(name) __device__ TraceRec name[kTraceMax]
-#define VA_TRACE_T(var) const unsigned long long var = wall_clock64()
-#define VA_TRACE_STORE(name, a, b, c, trips)                                                     \
-  do {                                                                                           \
-    if (threadIdx.x == 0 && blockIdx.x < kTraceMax) {                                            \
-      name[blockIdx.x].t0 = (a); name[blockIdx.x].t1 = (b); name[blockIdx.x].t2 = (c);           \
-      name[blockIdx.x].t3 = wall_clock64(); name[blockIdx.x].info = trace_where(trips);          \
-    }                                                                                            \
-  } while (0)
-#else
-#define VA_TRACE_DECL(name)
-#define VA_TRACE_T(var)
-#define VA_TRACE_STORE(name, a, b, c, trips)
-#endif
-
 }  // namespace va

@@ -10,31 +10,26 @@
 namespace va {
 namespace {
 
-template <typename T, int kVec> struct Chunk;
-template <> struct Chunk<float, 4> { typedef f32x4 type; };
-template <> struct Chunk<float, 1> { typedef float type; };
-template <> struct Chunk<uint16_t, 8> { typedef u32x4 type; };
-template <> struct Chunk<uint16_t, 1> { typedef uint16_t type; };
-
-__device__ __forceinline__ float elem(const f32x4 &v, int e) { return v[e]; }
-__device__ __forceinline__ float elem(const float &v, int) { return v; }
-__device__ __forceinline__ float elem(const uint16_t &v, int) { return bf16_to_f32(v); }
-__device__ __forceinline__ float elem(const u32x4 &v, int e) {
-  const uint32_t w = v[e >> 1];
-  return __uint_as_float((e & 1) ? (w & 0xffff0000u) : (w << 16));
-}
-__device__ __forceinline__ void put(f32x4 &v, int e, float lo, float) { v[e] = lo; }
-__device__ __forceinline__ void put(float &v, int, float lo, float) { v = lo; }
-__device__ __forceinline__ void put(uint16_t &v, int, float lo, float) { v = (uint16_t)(pack2_bf16(lo, 0.f) & 0xffffu); }
-__device__ __forceinline__ void put(u32x4 &v, int e, float lo, float hi) { v[e >> 1] = pack2_bf16(lo, hi); }
+// A chunk of kVec consecutive elements of type T (float, __bf16 or _Float16), 16 bytes when wide.
+template <typename T, int kVec> struct Chunk {
+  typedef T type __attribute__((ext_vector_type(kVec)));
+  static __device__ __forceinline__ float get(const type &v, int e) { return (float)v[e]; }
+  static __device__ __forceinline__ void set(type &v, int e, float x) { v[e] = (T)x; }  // round to nearest even
+};
+template <typename T> struct Chunk<T, 1> {
+  typedef T type;
+  static __device__ __forceinline__ float get(const type &v, int) { return (float)v; }
+  static __device__ __forceinline__ void set(type &v, int, float x) { v = (T)x; }
+};
 
 // One thread per (token, chunk of kVec pairs); it loops over the heads blockIdx.y, blockIdx.y +
 // gridDim.y, ... (the heads are split over gridDim.y when the token count alone cannot fill the chip).
 template <typename T, int kVec, typename IdT>
 __global__ void __launch_bounds__(256)
-rope_kernel(const T *__restrict__ x, T *__restrict__ y, const IdT *__restrict__ pos, long long n_work,
+rope_kernel(const T *x, T *y, const IdT *__restrict__ pos, long long n_work,  // y may be x (in place)
             int chunks_per_token, int H, int d, double neg2_log2base_over_d, int inverse) {
-  typedef typename Chunk<T, kVec>::type chunk_t;
+  typedef Chunk<T, kVec> C;
+  typedef typename C::type chunk_t;
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= n_work) return;
   const long long t = idx / chunks_per_token;
@@ -57,18 +52,11 @@ rope_kernel(const T *__restrict__ x, T *__restrict__ y, const IdT *__restrict__ 
   for (int h = blockIdx.y; h < H; h += hstep, xp += (size_t)hstep * d, yp += (size_t)hstep * d) {
     const chunk_t a = *(const chunk_t *)xp, b = *(const chunk_t *)(xp + hd);
     chunk_t ra, rb;
-    constexpr int kStep = (sizeof(T) == 2 && kVec > 1) ? 2 : 1;  // bf16 chunks are written as pairs
 #pragma unroll
-    for (int e = 0; e < kVec; e += kStep) {
-      float o1[2], o2[2];
-#pragma unroll
-      for (int u = 0; u < kStep; ++u) {
-        const float x1 = elem(a, e + u), x2 = elem(b, e + u);
-        o1[u] = x1 * cs[e + u] - x2 * sn[e + u];
-        o2[u] = x2 * cs[e + u] + x1 * sn[e + u];
-      }
-      put(ra, e, o1[0], o1[kStep - 1]);
-      put(rb, e, o2[0], o2[kStep - 1]);
+    for (int e = 0; e < kVec; ++e) {
+      const float x1 = C::get(a, e), x2 = C::get(b, e);
+      C::set(ra, e, x1 * cs[e] - x2 * sn[e]);
+      C::set(rb, e, x2 * cs[e] + x1 * sn[e]);
     }
     *(chunk_t *)yp = ra;
     *(chunk_t *)(yp + hd) = rb;
@@ -107,7 +95,8 @@ hipError_t pick(const void *x, void *y, const void *pos, va_itype it, long long 
 
 hipError_t launch_rope(const void *x, void *y, va_dtype dt, const void *pos, va_itype it, long long N,
                        int H, int d, double base, int inverse, hipStream_t stream) {
-  if (dt == VA_BF16) return pick<uint16_t, 8>(x, y, pos, it, N, H, d, base, inverse, stream);
+  if (dt == VA_BF16) return pick<__bf16, 8>(x, y, pos, it, N, H, d, base, inverse, stream);
+  if (dt == VA_F16) return pick<_Float16, 8>(x, y, pos, it, N, H, d, base, inverse, stream);
   return pick<float, 4>(x, y, pos, it, N, H, d, base, inverse, stream);
 }
 

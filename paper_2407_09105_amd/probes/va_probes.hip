@@ -1,8 +1,12 @@
-// Measurement aid: a loop of nothing but v_mfma_f32_32x32x16_bf16 on every SIMD of the chip.
-// Timed by the caller, it gives the matrix throughput this GPU actually sustains, to put next to
-// the published peak that the roofline fractions are quoted against.
-#include "va_internal.h"
-#include "va_mfma_common.h"
+// Measurement aids of the benchmark (libva_probes.so; no part of the attention library): what the
+// matrix pipe of this GPU sustains alone and in the company it keeps in the attention kernels.
+// First kernel: a loop of nothing but v_mfma_f32_32x32x16_bf16 on every SIMD of the chip.  Timed by
+// the caller, it gives the matrix throughput this GPU actually sustains, to put next to the
+// published peak that the roofline fractions are quoted against.
+#include <hip/hip_runtime.h>
+
+#include "va_probes.h"
+#include "../csrc/va_mfma_common.h"
 
 namespace va {
 namespace {
@@ -99,8 +103,8 @@ mix_probe_kernel(const uint32_t *__restrict__ operands, float *__restrict__ sink
 
 }  // namespace
 
-hipError_t launch_mix_probe(const void *operands, int lds_reads, int valu_groups, float *sink,
-                            unsigned long long *clocks, int iters, double *flops, hipStream_t stream) {
+static hipError_t launch_mix_probe(const void *operands, int lds_reads, int valu_groups, float *sink,
+                                   unsigned long long *clocks, int iters, double *flops, hipStream_t stream) {
   const uint32_t *op = (const uint32_t *)operands;
 #define VA_MIX(L, V) mix_probe_kernel<L, V><<<kProbeWgs, 256, 0, stream>>>(op, sink, clocks, iters)
   if (lds_reads == 0 && valu_groups == 0) VA_MIX(0, 0);
@@ -115,10 +119,32 @@ hipError_t launch_mix_probe(const void *operands, int lds_reads, int valu_groups
   return hipGetLastError();
 }
 
-hipError_t launch_mfma_probe(float *sink, int iters, double *flops, hipStream_t stream) {
+static hipError_t launch_mfma_probe(float *sink, int iters, double *flops, hipStream_t stream) {
   mfma_probe_kernel<<<kProbeWgs, 256, 0, stream>>>(sink, iters);
   if (flops) *flops = (double)kProbeWgs * 4.0 * (double)iters * kMfmaPerIter * (2.0 * 32 * 32 * 16);
   return hipGetLastError();
 }
 
 }  // namespace va
+
+extern "C" {
+
+int vap_probe_mfma(float *sink, int32_t iters, double *flops, void *stream) {
+  if (!sink) return VAP_ERR_NULL;
+  if (iters <= 0 || iters > (1 << 24)) return VAP_ERR_ARG;
+  return va::launch_mfma_probe(sink, iters, flops, (hipStream_t)stream) == hipSuccess ? VAP_OK : VAP_ERR_HIP;
+}
+
+int vap_probe_mix(const void *operands, int32_t lds_reads, int32_t valu_groups, float *sink, uint64_t *clocks,
+                  int32_t iters, double *flops, void *stream) {
+  if (!operands || !sink) return VAP_ERR_NULL;
+  if (iters <= 0 || iters > (1 << 24)) return VAP_ERR_ARG;
+  const bool known = (valu_groups == 0 && (lds_reads == 0 || lds_reads == 8 || lds_reads == 16)) ||
+                     (lds_reads == 16 && (valu_groups == 24 || valu_groups == 12)) ||
+                     (lds_reads == 8 && valu_groups == 16);
+  if (!known) return VAP_ERR_UNSUPPORTED;
+  return va::launch_mix_probe(operands, lds_reads, valu_groups, sink, (unsigned long long *)clocks, iters, flops,
+                              (hipStream_t)stream) == hipSuccess ? VAP_OK : VAP_ERR_HIP;
+}
+
+}  // extern "C"

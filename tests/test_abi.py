@@ -159,16 +159,23 @@ def test_attn_validation(L):
     assert L.va_attn_workspace_bytes(0, 2, 2, 16, 1) == 0
 
 
-def test_probe_validation(L):
-    """The measurement aids reject what they cannot run before launching anything."""
+def test_probe_library_is_separate_and_validates():
+    """The measurement aids live in their own library: the attention library exports none of them, the
+    probe library exports what its header declares and rejects what it cannot run before launching."""
+    from paper_2407_09105_amd import probes
+    text = open(os.path.join(ROOT, "paper_2407_09105_amd", "probes", "va_probes.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    assert sorted(set(re.findall(r"\b(vap_[a-z_0-9]+)\s*\(", text))) == sorted(probes.EXPORTS)
+    P = probes.lib()
+    assert not hasattr(binding.lib(), "va_probe_mfma") and not hasattr(binding.lib(), "vap_probe_mfma")
     p = C.c_void_p(0x1000)
-    assert L.va_probe_mfma(None, 10, None, None) == 1
-    assert L.va_probe_mfma(p, 0, None, None) == 2
-    assert L.va_probe_mix(None, 16, 24, p, None, 10, None, None) == 1
-    assert L.va_probe_mix(p, 16, 24, None, None, 10, None, None) == 1
-    assert L.va_probe_mix(p, 16, 24, p, None, 0, None, None) == 2
-    assert L.va_probe_mix(p, 5, 24, p, None, 10, None, None) == 3      # not an instantiated mix
-    assert L.va_probe_mix(p, 8, 24, p, None, 10, None, None) == 3
+    assert P.vap_probe_mfma(None, 10, None, None) == 1
+    assert P.vap_probe_mfma(p, 0, None, None) == 2
+    assert P.vap_probe_mix(None, 16, 24, p, None, 10, None, None) == 1
+    assert P.vap_probe_mix(p, 16, 24, None, None, 10, None, None) == 1
+    assert P.vap_probe_mix(p, 16, 24, p, None, 0, None, None) == 2
+    assert P.vap_probe_mix(p, 5, 24, p, None, 10, None, None) == 3      # not an instantiated mix
+    assert P.vap_probe_mix(p, 8, 24, p, None, 10, None, None) == 3
 
 
 def test_strings(L):

@@ -48,6 +48,19 @@ def test_bf16(shape):
     assert _rel_l2(got, ref) <= 3e-3
 
 
+@pytest.mark.parametrize("shape", [(515, 8, 128), (64, 4, 80), (9, 3, 10)])
+@pytest.mark.parametrize("inplace", [False, True])
+def test_fp16(shape, inplace):
+    rng = np.random.default_rng(sum(shape) + 2)
+    x = wl.round_to_f16(rng.standard_normal(shape).astype(np.float32))
+    pos = rng.integers(0, 16384, size=shape[0])
+    got = _run(x, pos, torch.float16, inplace=inplace)
+    ref = oracle.rope(x, pos)
+    # stored in fp16: half an ulp (2^-11 relative; 2^-25 absolute below the normal range)
+    assert np.all(np.abs(got - ref) <= 2.0 ** -10 * np.abs(ref) + 1e-6)
+    assert _rel_l2(got, ref) <= 5e-4
+
+
 def test_large_positions_int32_inplace_and_base():
     rng = np.random.default_rng(4)
     x = rng.standard_normal((64, 2, 32)).astype(np.float32)

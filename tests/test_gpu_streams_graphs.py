@@ -73,26 +73,28 @@ def test_graph_capture_and_replay():
         g.replay()
         torch.cuda.synchronize()
         got = _outputs(b)
+        if rep == 0:
+            for a, e in zip(got, ref):                  # the first replay reproduces the eager run before capture
+                assert torch.equal(a, e)
         _step(b)                                        # eager result on the same inputs
         torch.cuda.synchronize()
         for a, e in zip(got, _outputs(b)):
             assert torch.equal(a, e), rep
-    # the first replay reproduces the original eager run bit for bit
-    assert len(ref) == 7
 
 
 def test_measurement_probes_run_and_report():
     """The matrix-rate probes behind the benchmark's measured peaks: FLOP counts, clock read-out."""
+    from paper_2407_09105_amd import probes
     sink = torch.zeros(64, dtype=torch.float32, device=DEV)
-    assert binding.probe_mfma(sink, 10) == 2048 * 4 * 10 * 16 * 2.0 * 32 * 32 * 16
+    assert probes.probe_mfma(sink, 10) == 2048 * 4 * 10 * 16 * 2.0 * 32 * 32 * 16
     ops = torch.randn(32768, device=DEV).to(torch.bfloat16)
     clocks = torch.zeros(2, dtype=torch.int64, device=DEV)
     for lds, valu in ((0, 0), (16, 24), (8, 16)):
-        assert binding.probe_mix(ops, lds, valu, sink, clocks, 50) == 2048 * 4 * 50 * 16 * 2.0 * 32 * 32 * 16
+        assert probes.probe_mix(ops, lds, valu, sink, clocks, 50) == 2048 * 4 * 50 * 16 * 2.0 * 32 * 32 * 16
         torch.cuda.synchronize()
         c = clocks.cpu().numpy()
         assert c[0] > 0 and c[1] > 0
         assert 200.0 < c[0] / c[1] * 100.0 < 4000.0   # shader clock in MHz against the 100 MHz wall clock
     assert float(sink.abs().sum()) == 0.0
-    with pytest.raises(binding.VarlenAttnError):
-        binding.probe_mix(ops, 3, 3, sink, clocks, 10)
+    with pytest.raises(probes.ProbeError):
+        probes.probe_mix(ops, 3, 3, sink, clocks, 10)
