@@ -116,6 +116,28 @@ def test_bwd_is_deterministic():
         assert np.array_equal(a[key], b[key]), key
 
 
+def test_example_length_hints_change_speed_only():
+    # the dK/dV kernel's two workgroup shapes compute the same sums (the order of the query blocks
+    # differs): either hint, right or wrong for the batch, gives the default call's results up to fp32
+    # summation order
+    from paper_2407_09105_amd import binding
+    from tests.gpu_util import DEV, to_dev
+    for lengths in ([[1100, 1030]], [[17] * 30 + [2]]):
+        w = wl.make_custom(lengths, 4, 2, 128, "bf16", seed=15)
+        q, k, v, do = (to_dev(a, "bf16") for a in (w.q, w.k, w.v, w.do))
+        seg = binding.pack_to_cu_seqlens(torch.from_numpy(w.position_ids).to(DEV))
+        o, lse = binding.varlen_attn_fwd(q, k, v, seg)
+        ref = binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, grad_dtype=torch.float32)
+        all_stages = binding.STAGE_D | binding.STAGE_DQ | binding.STAGE_DKDV
+        for hint in (binding.HINT_LONG_EXAMPLES, binding.HINT_SHORT_EXAMPLES):
+            got = binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, grad_dtype=torch.float32, stages=all_stages | hint)
+            torch.cuda.synchronize()
+            for name, a, b in zip(("dQ", "dK", "dV"), got, ref):
+                assert torch.allclose(a, b, rtol=1e-4, atol=1e-4), (name, hint, lengths)
+        with pytest.raises(binding.VarlenAttnError):      # both hints at once
+            binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, stages=all_stages | 24)
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_shapes(seed):
     # seeded random rows / row lengths / example lengths / head counts / head dims / element types:
