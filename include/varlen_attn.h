@@ -175,6 +175,25 @@ va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const
                              size_t workspace_bytes, void *stream);
 
 /*
+ * The backward above for callers that cannot allocate device memory or pass a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results
+ * and errors as va_varlen_attn_bwd, without `workspace`: D lives in a device array inside the library
+ * (VA_NOALLOC_SCRATCH_BYTES per GPU, held until the process ends).  Calls no hipMalloc / hipFree and no
+ * allocating routine; the first call on a device looks the array's address up once (make that call
+ * outside stream capture).
+ *   Limit: rows * tokens_per_row * hq * 4 <= VA_NOALLOC_SCRATCH_BYTES, else VA_ERR_WORKSPACE and
+ *   nothing is enqueued.
+ *   All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ *   streams, or threads) race; calls enqueued on one stream are safe.
+ */
+#define VA_NOALLOC_SCRATCH_BYTES (32u << 20)
+va_status va_varlen_attn_bwd_noalloc(const void *dO, const void *Q, const void *K, const void *V,
+                                     const void *O, const float *LSE, void *dQ, void *dK, void *dV,
+                                     va_dtype grad_dt, const va_segments *seg, int32_t rows,
+                                     int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
+                                     va_dtype dt, float softmax_scale, void *stream);
+
+/*
  * The backward in parts, so that a caller can time its kernels one by one with events on `stream`:
  * `stages` is an OR of the flags below.
  *   VA_STAGE_D    D = rowsum(dO * O) into `workspace`.

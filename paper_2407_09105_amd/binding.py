@@ -25,7 +25,8 @@ HINT_LONG_EXAMPLES, HINT_SHORT_EXAMPLES = 8, 16
 
 EXPORTS = (
     "va_plan_bytes", "va_segments_bind", "va_pack_to_cu_seqlens", "va_attn_workspace_bytes",
-    "va_varlen_attn_fwd", "va_varlen_attn_bwd", "va_varlen_attn_bwd_stages", "va_collate_padding_free",
+    "va_varlen_attn_fwd", "va_varlen_attn_bwd", "va_varlen_attn_bwd_stages", "va_varlen_attn_bwd_noalloc",
+    "va_collate_padding_free",
     "va_rope_apply", "va_status_string", "va_version",
 )
 
@@ -64,6 +65,9 @@ def lib() -> C.CDLL:
         C.c_int, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
     L.va_varlen_attn_bwd_stages.restype = C.c_int
     L.va_varlen_attn_bwd_stages.argtypes = L.va_varlen_attn_bwd.argtypes + [C.c_uint32]
+    L.va_varlen_attn_bwd_noalloc.restype = C.c_int
+    L.va_varlen_attn_bwd_noalloc.argtypes = [C.c_void_p] * 9 + [C.c_int, C.POINTER(VaSegments)] + [C.c_int32] * 5 + [
+        C.c_int, C.c_float, C.c_void_p]
     L.va_collate_padding_free.restype = C.c_int
     L.va_collate_padding_free.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_int32, C.c_int32,
                                           C.c_int32, C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -310,3 +314,25 @@ def varlen_attn_bwd(do, q, k, v, o, lse, seg: Segments, softmax_scale: float = 0
         _check("va_varlen_attn_bwd_stages", lib().va_varlen_attn_bwd_stages(*args, int(stages)))
     return dq, dk, dv
 
+
+NOALLOC_SCRATCH_BYTES = 32 << 20
+
+
+def varlen_attn_bwd_noalloc(do, q, k, v, o, lse, seg: Segments, dq, dk, dv, softmax_scale: float = 0.0):
+    """The backward through the entry point that allocates nothing: the caller passes every output,
+    D lives in the library's own device array (N * Hq * 4 <= NOALLOC_SCRATCH_BYTES).  No tensor is
+    created here either."""
+    _need_cuda(do, q, k, v, o, lse, dq, dk, dv)
+    N, hq, hkv, d = _shapes(q, k, v, seg)
+    if not (q.dtype == k.dtype == v.dtype == o.dtype == do.dtype):
+        raise TypeError("dO, Q, K, V, O must share a dtype")
+    if lse.dtype != torch.float32 or tuple(lse.shape) != (hq, N):
+        raise ValueError("LSE must be float32 [Hq, N]")
+    _out_like("dq", dq, q.shape, dq.dtype, q.device)
+    _out_like("dk", dk, k.shape, dq.dtype, q.device)
+    _out_like("dv", dv, v.shape, dq.dtype, q.device)
+    _check("va_varlen_attn_bwd_noalloc", lib().va_varlen_attn_bwd_noalloc(
+        do.data_ptr(), q.data_ptr(), k.data_ptr(), v.data_ptr(), o.data_ptr(), lse.data_ptr(),
+        dq.data_ptr(), dk.data_ptr(), dv.data_ptr(), _dt(dq), C.byref(seg.c), seg.rows, seg.tokens_per_row,
+        hq, hkv, d, _dt(q), float(softmax_scale), _stream()))
+    return dq, dk, dv

@@ -1,6 +1,7 @@
 // C ABI of the library: argument validation and dispatch.  See include/varlen_attn.h.
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 #include "va_internal.h"
 
@@ -216,6 +217,50 @@ va_status va_varlen_attn_bwd(const void *dO, const void *Q, const void *K, const
   return va_varlen_attn_bwd_stages(dO, Q, K, V, O, LSE, dQ, dK, dV, grad_dt, seg, rows, tokens_per_row, hq,
                                    hkv, d, dt, softmax_scale, workspace, workspace_bytes, stream,
                                    VA_STAGE_D | VA_STAGE_DKDV | VA_STAGE_DQ);
+}
+
+// ---- the backward for callers that cannot allocate ------------------------------------------
+// Its workspace (D = rowsum(dO * O), [Hq, N] float) is this file-scope device array instead of a
+// caller's buffer.  Every GPU holds its own copy at its own address: the address is looked up once
+// per device (hipGetSymbolAddress with that device current) and only that pointer is ever handed to
+// a kernel - the array's name is a host-side stand-in, not a device address.
+static __device__ __align__(256) unsigned char scratch[VA_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];  // per device: address of `scratch` there, once looked up
+
+// Address of this device's copy of `scratch` (nullptr on error).
+void *scratch_on_current_device() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = p;
+  }
+  return g_scratch_ptr[dev];
+}
+}  // namespace
+
+va_status va_varlen_attn_bwd_noalloc(const void *dO, const void *Q, const void *K, const void *V,
+                                     const void *O, const float *LSE, void *dQ, void *dK, void *dV,
+                                     va_dtype grad_dt, const va_segments *seg, int32_t rows,
+                                     int32_t tokens_per_row, int32_t hq, int32_t hkv, int32_t d,
+                                     va_dtype dt, float softmax_scale, void *stream) {
+  const va_status s = check_bwd(dO, Q, K, V, O, LSE, dQ, dK, dV, grad_dt, seg, rows, tokens_per_row, hq, hkv, d, dt,
+                                 VA_STAGE_D | VA_STAGE_DKDV | VA_STAGE_DQ);
+  if (s != VA_OK) return s;  // before anything touches the GPU
+  const size_t need = va_attn_workspace_bytes(rows * tokens_per_row, hq, hkv, d, 1);
+  if (need == 0 || need > (size_t)VA_NOALLOC_SCRATCH_BYTES) return VA_ERR_WORKSPACE;  // beyond the static array
+  void *ws = scratch_on_current_device();
+  if (!ws) return VA_ERR_HIP;
+  // every byte of D that the dK/dV kernel reads is written by the dQ (or D) kernel of the same call,
+  // so nothing of the previous call's contents has to be cleared
+  return va_varlen_attn_bwd(dO, Q, K, V, O, LSE, dQ, dK, dV, grad_dt, seg, rows, tokens_per_row, hq, hkv, d, dt,
+                            softmax_scale, ws, (size_t)VA_NOALLOC_SCRATCH_BYTES, stream);
 }
 
 const char *va_status_string(va_status s) {

@@ -159,6 +159,28 @@ def test_attn_validation(L):
     assert L.va_attn_workspace_bytes(0, 2, 2, 16, 1) == 0
 
 
+def test_noalloc_backward_validation(L):
+    """The backward that allocates nothing validates on the host before it touches the GPU: bad
+    arguments and sizes beyond its device array are refused with nothing looked up or launched."""
+    seg = _bound(L)
+    p = 0x20000
+    f = L.va_varlen_attn_bwd_noalloc
+    ok = [p] * 9 + [binding.VA_F32, C.byref(seg), 1, 16, 2, 2, 16, binding.VA_F32, 0.0, None]
+
+    def with_(i, val):
+        a = list(ok)
+        a[i] = val
+        return a
+
+    assert f(*with_(0, None)) == 1 and f(*with_(8, None)) == 1 and f(*with_(10, None)) == 1
+    assert f(*with_(13, 3)) == 2                           # Hq % Hkv != 0
+    assert f(*with_(9, 5)) == 3                            # unknown gradient type
+    big = list(ok)
+    big[11], big[12], big[13], big[14] = 8, 8192, 256, 256  # D = 65536 tokens x 256 heads x 4 B = 64 MiB
+    assert 8 * 8192 * 256 * 4 > binding.NOALLOC_SCRATCH_BYTES
+    assert f(*big) == 4                                    # beyond the library's array
+
+
 def test_probe_library_is_separate_and_validates():
     """The measurement aids live in their own library: the attention library exports none of them, the
     probe library exports what its header declares and rejects what it cannot run before launching."""
