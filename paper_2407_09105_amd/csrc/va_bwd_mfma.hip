@@ -36,9 +36,9 @@ constexpr float kLog2e = 1.4426950408889634f;
 // residuals are below 2^-9 of those thresholds and are dropped.  fp16 operands (11 bits) need none.
 constexpr float kSplitP = 0.125f;
 constexpr float kSplitS = 1.0f;
-// Queries whose whole context is shorter than this get their dQ corrected for the rounding of O in
+// Waves holding queries with fewer keys than this correct their dQ for the rounding of O in
 // D = dO . O (see dq_mfma_kernel).
-constexpr int kNearCtx = 64;
+constexpr int kNearCtx = 32;
 
 template <class E> struct needs_split { static constexpr bool value = false; };
 template <> struct needs_split<Bf16> { static constexpr bool value = true; };
@@ -253,7 +253,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
         }
       }
     }
-    __syncthreads();
+    if (jb < jb_hi) __syncthreads();  // workgroup-uniform; the last block's barrier follows the correction pass below
   };
 
   for (int jb = jb_lo; jb <= jb_hi; jb += 2) {  // bounds are workgroup-uniform: barriers stay aligned
@@ -267,59 +267,45 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   const float c_row = pair_sum(csum);
   if (row_ok && half == 0) delta[(size_t)h * N + i_abs] = dl + c_row;
   // dQ was accumulated with D~: what is missing is -c_i sum_j P_ij k_j.  It matters where the
-  // probabilities are large, i.e. for queries with a short context (it falls off as 1 / context^2);
-  // waves that hold queries with fewer than kNearCtx keys recompute P on the key sub-blocks from
-  // kNearCtx before their first row on and add K^T (-c P)^T.  Those keys span at most four blocks,
-  // which the stage memory holds at once.
-  const bool near_start = wave_ok && ss_max > iw0 - kNearCtx;  // wave-uniform
-  if (__syncthreads_or(near_start)) {                           // workgroup-uniform; the loop's last barrier freed the stages
-    const int jb_c0 = max(jb_lo, max(t0 - kNearCtx, 0) / kBS);  // jb_hi - jb_c0 <= 3
-#pragma unroll
-    for (int n = 0; n < 4; ++n) {
-      if (jb_c0 + n > jb_hi) break;  // workgroup-uniform
-      const uint32_t off = dma_off + (uint32_t)(jb_c0 + n - jb_lo) * blk_bytes;
-#pragma unroll
-      for (int hf = 0; hf < kHf; ++hf)
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-          const uint32_t o = dma_ok[hf] ? off + p * p_bytes + hf * 256 : kPastEnd;
-          __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(lds + n * kBlkT + hf * kBlk + (4 * p + wave) * 512), 16, o, 0, 0, 0);
-        }
-    }
-    wait_all_loads();
-    __syncthreads();
-    if (near_start) {
-      const int j_first = max(ss_min, iw0 - kNearCtx);
-      for (int n = 0; n < 4 && jb_c0 + n <= jb_hi; ++n) {
-        const uint16_t *Kb = lds + n * kBlkT;
+  // probabilities are large, i.e. for queries with a short context (it falls off as 1 / context^2).
+  // Waves that hold queries with fewer than kNearCtx keys recompute P on the key sub-blocks from
+  // kNearCtx before their first row on and add K^T (-c P)^T - on the last two key blocks only, which
+  // are still in the stage memory (nothing was copied after them): no copy, no extra barrier.  A
+  // short-context query at the very start of a tile whose example began in an earlier block keeps
+  // the part of the correction that belongs to those earlier keys (its dQ then carries the 1e-2-size
+  // trace of the rounded O that every query carried before).
+  if (wave_ok && ss_max > iw0 - kNearCtx) {  // wave-uniform
+    const int j_first = max(ss_min, iw0 - kNearCtx);
 #pragma unroll 1
-        for (int sb = 0; sb < 2; ++sb) {
-          const int jl = (jb_c0 + n) * kBS + sb * 32;
-          if (jl > iw1 || jl + 31 < j_first) continue;  // wave-uniform
-          f32x16 sc;
+    for (int jb = max(jb_lo, jb_hi - 1); jb <= jb_hi; ++jb) {
+      const uint16_t *Kb = ((jb - jb_lo) & 1) ? K1 : K0;
+#pragma unroll 1
+      for (int sb = 0; sb < 2; ++sb) {
+        const int jl = jb * kBS + sb * 32;
+        if (jl > iw1 || jl + 31 < j_first) continue;  // wave-uniform
+        f32x16 sc;
 #pragma unroll
-          for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+        for (int v = 0; v < 16; ++v) sc[v] = 0.f;
 #pragma unroll
-          for (int ks = 0; ks < kKs; ++ks)
-            sc = mfma32(swz_read_row<E>(Kb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32), qf[ks], sc);
+        for (int ks = 0; ks < kKs; ++ks)
+          sc = mfma32(swz_read_row<E>(Kb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32), qf[ks], sc);
 #pragma unroll
-          for (int v = 0; v < 16; ++v) {
-            const int j = jl + acc_row(v, half);
-            const float p = __builtin_amdgcn_exp2f(fmaf(sc[v], scale_log2, -lse2));
-            sc[v] = (j < ss_i || j > i_abs) ? 0.f : -c_row * p;
-          }
+        for (int v = 0; v < 16; ++v) {
+          const int j = jl + acc_row(v, half);
+          const float p = __builtin_amdgcn_exp2f(fmaf(sc[v], scale_log2, -lse2));
+          sc[v] = (j < ss_i || j > i_abs) ? 0.f : -c_row * p;
+        }
 #pragma unroll
-          for (int s2 = 0; s2 < 2; ++s2) {
-            const x8 cf = pack_x8<E>(sc, 8 * s2);
+        for (int s2 = 0; s2 < 2; ++s2) {
+          const x8 cf = pack_x8<E>(sc, 8 * s2);
 #pragma unroll
-            for (int cb = 0; cb < kCb; ++cb)
-              acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + s2 * 16), cf, acc[cb]);
-          }
+          for (int cb = 0; cb < kCb; ++cb)
+            acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + s2 * 16), cf, acc[cb]);
         }
       }
     }
-    __syncthreads();  // the result staging below overlays the blocks just read
   }
+  __syncthreads();  // every wave is done with the stages: the result staging below overlays them
   float *stage = (float *)lds + wave * kStageFloatsPerWave;
   store_transposed_tile<EOut, kCb>(acc, scale, stage, dQ, iw0, wave_ok ? iw1 - iw0 + 1 : 0, hq, h, d);
 }
