@@ -52,6 +52,8 @@ typedef enum { VA_I32 = 0, VA_I64 = 1 } va_itype;   /* element type of position_
 
 /* The tile schedule is expressed in tiles of this many consecutive tokens of a packed row. */
 #define VA_TILE 256
+/* Tile index of a q_tile_order / kv_tile_order entry. */
+#define VA_ORDER_TILE(entry) ((entry) & 0xffffff)
 
 /*
  * Example boundaries and tile schedule of one packed stream.  A host struct of
@@ -64,9 +66,11 @@ typedef struct va_segments {
   int32_t *seg_start;     /* [N]  first token of that example  (= cu[seg_id[t]])                         */
   int32_t *seg_end;       /* [N]  one past its last token      (= cu[seg_id[t] + 1])                     */
   int32_t *meta;          /* [8]  meta[0] = n (examples), meta[1] = max_seqlen; rest reserved            */
-  int32_t *q_tile_order;  /* [R * ceil(T / VA_TILE)] query tiles: tiles of the longest examples first,   */
-  int32_t *kv_tile_order; /* ... key tiles likewise; tiles of one example adjacent, heaviest first;      */
-                          /* tiles of examples of at most VA_TILE tokens come last, in stream order      */
+  int32_t *q_tile_order;  /* [R * ceil(T / VA_TILE)] query tiles in launch order: tiles of the longest examples  */
+  int32_t *kv_tile_order; /* first, tiles of one example adjacent, heaviest first; tiles of examples of at most   */
+                          /* VA_TILE tokens last, in stream order.  Key tiles likewise.  Entry: tile index in    */
+                          /* bits 0..23 (VA_ORDER_TILE), bits 24..30 the tile's head rotation (which head runs   */
+                          /* on which XCD: one value per long example, rank / 8 for short ones)                  */
   int32_t *scratch;       /* internal: per-chunk partial scans and tile costs                            */
 } va_segments;
 

@@ -162,7 +162,9 @@ class Segments:
             "cu_seqlens": self.cu_seqlens_capacity[: n + 1].cpu().numpy(),
             "seg_id": self.seg_id.cpu().numpy(), "seg_start": self.seg_start.cpu().numpy(),
             "seg_end": self.seg_end.cpu().numpy(),
-            "q_tile_order": self.q_tile_order.cpu().numpy(), "kv_tile_order": self.kv_tile_order.cpu().numpy(),
+            # order entries: tile index in bits 0..23, the tile's head rotation above
+            "q_tile_order": self.q_tile_order.cpu().numpy() & 0xFFFFFF, "kv_tile_order": self.kv_tile_order.cpu().numpy() & 0xFFFFFF,
+            "q_tile_rotation": self.q_tile_order.cpu().numpy() >> 24, "kv_tile_rotation": self.kv_tile_order.cpu().numpy() >> 24,
         }
 
 

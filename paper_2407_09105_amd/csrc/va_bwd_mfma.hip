@@ -85,9 +85,10 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   const int l32 = lane & 31, half = lane >> 5;
   // schedule tiles hold kSub workgroup tiles; workgroups of one schedule tile are adjacent
   const int wg = xcd_group_remap(blockIdx.x, hq / hkv, gridDim.x);
-  const int tile = uniform(q_tile_order[wg / (hq * kSub)]);
+  const int entry = uniform(q_tile_order[wg / (hq * kSub)]);
+  const int tile = order_tile(entry);
   const int sub = (wg / hq) % kSub;
-  const int h = (wg % hq + head_rotation(wg / (hq * kSub)) * (hq / hkv)) % hq;
+  const int h = (wg % hq + head_rotation(entry) * (hq / hkv)) % hq;
   const int g = h / (hq / hkv);
   const int r = tile / tiles_per_row, m = tile % tiles_per_row;
   const int row_end = (r + 1) * T;
@@ -382,9 +383,10 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   const int kg = wave % kKg;
   const bool k_side = wave >= kKg;
   const int l32 = lane & 31, half = lane >> 5;
-  const int tile = uniform(kv_tile_order[blockIdx.x / (hkv * kSubTiles)]);
+  const int entry = uniform(kv_tile_order[blockIdx.x / (hkv * kSubTiles)]);
+  const int tile = order_tile(entry);
   const int sub = (blockIdx.x / hkv) % kSubTiles;
-  const int g = (blockIdx.x % hkv + head_rotation(blockIdx.x / (hkv * kSubTiles))) % hkv;
+  const int g = (blockIdx.x % hkv + head_rotation(entry)) % hkv;
   const int G = hq / hkv;
   const int r = tile / tiles_per_row, m = tile % tiles_per_row;
   const int row_end = (r + 1) * T;

@@ -57,9 +57,10 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
 
   // heavy schedule tiles first; the workgroups of one schedule tile (sub-tiles x heads) are adjacent
   const int wg = xcd_group_remap(blockIdx.x, hq / hkv, gridDim.x);
-  const int tile = uniform(q_tile_order[wg / (hq * kSub)]);
+  const int entry = uniform(q_tile_order[wg / (hq * kSub)]);
+  const int tile = order_tile(entry);
   const int sub = (wg / hq) % kSub;
-  const int h = (wg % hq + head_rotation(wg / (hq * kSub)) * (hq / hkv)) % hq;
+  const int h = (wg % hq + head_rotation(entry) * (hq / hkv)) % hq;
   const int g = h / (hq / hkv);
   const int r = tile / tiles_per_row, m = tile % tiles_per_row;
   const int row_end = (r + 1) * T;  // one past the last token of this packed row

@@ -95,16 +95,14 @@ __device__ __forceinline__ int xcd_group_remap(int wg, int G, int n_wg) {
   return ((slot / G) * 8 + xcd) * G + slot % G;
 }
 
-// Workgroup w runs on XCD w % 8, and the workgroups of one schedule tile are numbered head by head:
-// with a head count that is a multiple of 8 every XCD would serve the same heads of every tile, i.e.
-// always the same 256-byte columns of the token rows, which map to a fixed subset of the memory
-// channels - some of them far from that XCD (measured on examples of 8..128 tokens, where the
-// kernels are bound by HBM: two XCDs ran 20 % slower than the rest and every launch waited for
-// them).  The heads (KV-head groups) of a schedule tile are therefore rotated by this amount, which
-// advances every 8 schedule tiles in launch order: over a launch every XCD meets every head, while
-// the tiles of one example - neighbours in launch order - mostly keep their XCD and its L2
-// (rotating every tile cost 3 % where the data is L2-resident).
-__device__ __forceinline__ int head_rotation(int order_index) { return order_index >> 3; }
+// A tile-order entry of the pack: tile index in bits 0..23, head rotation of the tile above.
+// Workgroup w runs on XCD w % 8, and the workgroups of one schedule tile are numbered head by head;
+// the heads (KV-head groups) of the tile are rotated by this amount, which is the same for all tiles of
+// one long example (each head's K/V or Q/dO stream then stays in one XCD's L2) and advances with the
+// launch order among tiles of short examples (every XCD meets every head and with it every memory
+// channel): the boundary scan decides, see order_entry there.
+__device__ __forceinline__ int order_tile(int entry) { return entry & 0xffffff; }
+__device__ __forceinline__ int head_rotation(int entry) { return (entry >> 24) & 127; }
 
 // Wave-uniform value -> scalar register, so that conditions on it compile to scalar branches.
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }

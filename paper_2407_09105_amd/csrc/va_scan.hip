@@ -217,6 +217,23 @@ __device__ __forceinline__ unsigned long long tile_key(int len, int start, int c
   return ((unsigned long long)(len <= kShortExample ? 0 : min(len, (1 << 20) - 1)) << 43) |
          ((unsigned long long)(0x7fffffff - start) << 12) | (unsigned long long)min(cost, 4095);
 }
+// An order entry carries, above the tile index (bits 0..23), the head rotation of its tile (bits
+// 24..30; see head_rotation in va_mfma_common.h).  Tiles of an example longer than a schedule tile
+// all get one rotation, derived from the example's first token: workgroup w runs on XCD w % 8 and the
+// rotation decides which head lands on which XCD, so the tiles of one example - which stream the same
+// K/V (or Q/dO) rows - keep each head on one XCD and fetch its rows into one L2 only, while different
+// examples start from different rotations.  Tiles of short examples take their rank / 8: over a
+// launch every XCD then meets every head (with a fixed assignment every XCD would always read the
+// same 256-byte columns of the token rows, i.e. a fixed subset of the memory channels; measured on
+// examples of 8..128 tokens, where the kernels are bound by HBM: two XCDs ran 20 % slower than the
+// rest), while neighbours in launch order still mostly share an XCD.
+__device__ __forceinline__ int32_t order_entry(int tile, unsigned long long key, int rank) {
+  const unsigned len_class = (unsigned)(key >> 43);
+  const unsigned start = 0x7fffffffu - (unsigned)((key >> 12) & 0x7fffffffu);
+  const unsigned rot = len_class ? (start / kTile) * 5u + (start >> 13) : (unsigned)rank >> 3;
+  return (int32_t)((unsigned)tile | ((rot & 127u) << 24));
+}
+
 __global__ void __launch_bounds__(256)
 tile_cost_kernel(const int32_t *__restrict__ seg_start, const int32_t *__restrict__ seg_end, int T,
                  int tiles_per_row, int ntiles, unsigned long long *__restrict__ key_q,
@@ -251,7 +268,7 @@ tile_rank_kernel(const unsigned long long *__restrict__ cost_q, const unsigned l
     }
     __syncthreads();
   }
-  if (tile < ntiles) { order_q[rq] = tile; order_kv[rkv] = tile; }
+  if (tile < ntiles) { order_q[rq] = order_entry(tile, cq, rq); order_kv[rkv] = order_entry(tile, ckv, rkv); }
 }
 
 // ---- two-launch path for streams of up to kOnePassMaxChunks chunks --------------------------------
@@ -396,8 +413,8 @@ tile_order_fused_kernel(const int32_t *__restrict__ seg_start, const int32_t *__
     rq += (s_q[o] > cq) || (s_q[o] == cq && o < tile);
     rkv += (s_kv[o] > ckv) || (s_kv[o] == ckv && o < tile);
   }
-  order_q[rq] = tile;
-  order_kv[rkv] = tile;
+  order_q[rq] = order_entry(tile, cq, rq);
+  order_kv[rkv] = order_entry(tile, ckv, rkv);
 }
 
 // ---- one launch for streams of up to kSingleMaxTokens tokens -----------------------------------
@@ -513,8 +530,8 @@ pack_single_kernel(const IdT *__restrict__ pos, int N, int T, int tiles_per_row,
       rq += (s_q[o] > cq) || (s_q[o] == cq && o < tile);
       rkv += (s_kv[o] > ckv) || (s_kv[o] == ckv && o < tile);
     }
-    order_q[rq] = tile;
-    order_kv[rkv] = tile;
+    order_q[rq] = order_entry(tile, cq, rq);
+    order_kv[rkv] = order_entry(tile, ckv, rkv);
   }
 }
 

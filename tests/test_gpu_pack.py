@@ -44,6 +44,23 @@ def _check_orders(got, pos_np):
         # largest key first, ties keep index order: the result is unique
         expect = np.lexsort((tiles, -k))
         assert np.array_equal(order, expect), name
+    # Design properties of the schedule, stated without the sort key: tiles governed by examples longer
+    # than a schedule tile come first, longest example first, the tiles of one example adjacent and
+    # sharing one head rotation; tiles of shorter examples follow in stream order, rotation = rank / 8.
+    for name, rot_name, gov in (("q_tile_order", "q_tile_rotation", t0), ("kv_tile_order", "kv_tile_rotation", t1)):
+        order, rot = got[name], got[rot_name]
+        glen = (se[gov] - ss[gov])[order]          # length of each tile's governing example, in launch order
+        gstart = ss[gov][order]
+        long_ = glen > TILE
+        n_long = int(long_.sum())
+        assert long_[:n_long].all() and not long_[n_long:].any()
+        assert np.all(np.diff(glen[:n_long]) <= 0)                       # longest first
+        runs = np.flatnonzero(np.diff(gstart[:n_long]) != 0) + 1         # where the governing example changes
+        assert len(set(gstart[:n_long].tolist())) == len(runs) + (1 if n_long else 0)   # one run per example: adjacent
+        for a, b in zip(np.r_[0, runs], np.r_[runs, n_long]) if n_long else ():
+            assert len(set(rot[a:b].tolist())) == 1                      # one rotation per long example
+        assert np.array_equal(order[n_long:], np.sort(order[n_long:]))   # short ones: stream order
+        assert np.array_equal(rot[n_long:], (np.arange(n_long, nt) >> 3) & 127)
 
 
 def test_worked_example(worked_example):
