@@ -66,6 +66,33 @@ def test_nothing_is_written_outside_the_outputs(lengths, hq, hkv, d, dtype, gdt)
     assert_close(got, ref, dtype, bf16_stored=("dQ", "dK", "dV") if gdt != torch.float32 else ())
 
 
+def test_binding_refuses_output_buffers_the_library_would_overrun():
+    # the library only gets pointers: a caller-supplied output of the wrong type, shape or layout must not reach it
+    w = wl.make_custom([[40, 24]], 4, 2, 64, "bf16", seed=3)
+    q, k, v, do = (to_dev(a, "bf16") for a in (w.q, w.k, w.v, w.do))
+    seg = binding.pack_to_cu_seqlens(torch.from_numpy(w.position_ids).to(DEV))
+    o, lse = binding.varlen_attn_fwd(q, k, v, seg)
+    f32 = lambda t: torch.empty(t.shape, dtype=torch.float32, device=DEV)
+    with pytest.raises(ValueError):
+        binding.varlen_attn_fwd(q, k, v, seg, out=f32(q))                          # fp32 out for bf16 inputs
+    with pytest.raises(ValueError):
+        binding.varlen_attn_fwd(q, k, v, seg, lse=torch.empty((64, 4), dtype=torch.float32, device=DEV))   # transposed LSE
+    with pytest.raises(ValueError):
+        binding.varlen_attn_fwd(q, k, v, seg, out=torch.empty((64, 8, 64), dtype=q.dtype, device=DEV)[:, ::2])  # not contiguous
+    with pytest.raises(ValueError):
+        binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, dq=f32(q), dk=f32(q), dv=f32(v))   # dK of dQ's shape under GQA
+    with pytest.raises(ValueError):
+        binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, dq=f32(q), dk=torch.empty_like(k), dv=f32(v))   # mixed gradient types
+    with pytest.raises(ValueError):
+        binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, workspace=torch.empty(64 * 4, dtype=torch.float16, device=DEV))
+    with pytest.raises(ValueError):
+        binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, workspace=torch.empty(10, dtype=torch.float32, device=DEV))
+    with pytest.raises(ValueError):
+        binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, dq=torch.empty(q.shape, dtype=torch.float32))   # host tensor
+    dq, dk, dv = binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, dq=f32(q), dk=f32(k), dv=f32(v))   # fp32 grads by example
+    assert dq.dtype == torch.float32 and bool(torch.isfinite(dk).all())
+
+
 def test_plan_buffer_is_not_overrun():
     # the scan writes cu_seqlens, per-token arrays, tile orders and its scratch inside va_plan_bytes
     for R, T in ((1, 16), (3, 319), (1, 8192), (2, 9000), (5, 20000)):
