@@ -7,6 +7,7 @@ import torch
 
 from oracle import oracle
 from paper_2407_09105_amd import binding
+from tests.conftest import progress
 
 DEV = "cuda:0"
 
@@ -89,7 +90,7 @@ def run_oracle_in_steps(w, long_pairs=4_000_000, heads_per_call=16):
         O[idx], lse = oracle.fwd(q, k, v, cu_s)
         LSE[:, idx] = lse
         dQ[idx], dK[idx], dV[idx] = oracle.bwd(do, q, k, v, cu_s)
-        print(f"   oracle: {short.size} examples of fewer than {long_pairs} pairs done, {time.time() - t0:.0f} s", flush=True)
+        progress(f"   oracle: {short.size} examples of fewer than {long_pairs} pairs done, {time.time() - t0:.0f} s")
     for s in np.flatnonzero(pairs >= long_pairs):
         a, b = int(cu[s]), int(cu[s + 1])
         cu_1 = np.array([0, b - a], dtype=np.int32)
@@ -103,7 +104,7 @@ def run_oracle_in_steps(w, long_pairs=4_000_000, heads_per_call=16):
             dQ[a:b, hs] = dq
             np.add.at(dK[a:b], (slice(None), hs // G), dk)
             np.add.at(dV[a:b], (slice(None), hs // G), dv)
-            print(f"   oracle: example of {b - a} tokens, query heads {h0}..{hs[-1]} done, {time.time() - t0:.0f} s", flush=True)
+            progress(f"   oracle: example of {b - a} tokens, query heads {h0}..{hs[-1]} done, {time.time() - t0:.0f} s")
     return {"seg": seg, "O": O, "LSE": LSE, "dQ": dQ, "dK": dK, "dV": dV}
 
 

@@ -15,6 +15,7 @@ import torch
 
 from oracle import oracle
 from paper_2407_09105_amd import binding, workloads as wl
+from tests.conftest import progress
 from tests.gpu_util import (BF16_MAX_ABS, BF16_REL_L2, DEV, assert_close, assert_seg_equal, max_abs, rel_l2,
                             run_gpu, run_oracle, run_oracle_in_steps, to_dev)
 
@@ -26,10 +27,10 @@ def full_case(request):
     """(workload, oracle results) of one configuration; the oracle runs once per configuration
     (config 5 is 6 TFLOP of fp64 work: minutes on the host cores)."""
     w = wl.make_workload(request.param)
-    print(f"config {request.param}:", w.stats, "- running the oracle in full", flush=True)
+    progress(f"config {request.param}: {w.stats} - running the oracle in full")
     t0 = time.time()
     ref = run_oracle_in_steps(w)
-    print(f"   oracle: {time.time() - t0:.0f} s on {oracle.num_threads()} threads", flush=True)
+    progress(f"   oracle: {time.time() - t0:.0f} s on {oracle.num_threads()} threads")
     return w, ref
 
 
