@@ -138,6 +138,29 @@ def test_example_length_hints_change_speed_only():
             binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, stages=all_stages | 24)
 
 
+@pytest.mark.parametrize("gain", [2.0, 3.0])
+def test_peaked_softmax(gain):
+    # Q and K scaled up: scores of standard deviation gain^2, so most rows put nearly all their weight on
+    # one or two keys (what trained models do, unlike N(0,1) inputs).  The forward's reference maximum
+    # moves, P has entries near 1 deep inside long examples, dS is a small difference of large terms.
+    # The relative-L2 bar is scale-free and must hold; dK and dV, whose large entries go through the
+    # matrix pipe in two parts, also keep the absolute bar although the gradients are gain times larger.
+    w = wl.make_custom([[300, 45, 1, 1, 200, 93, 600]], 8, 2, 128, "bf16", seed=21)
+    w.q, w.k = wl.round_to_bf16(w.q * gain), wl.round_to_bf16(w.k * gain)
+    got = run_gpu(w, grad_dtype=torch.float32, nan_fill=True)
+    ref = run_oracle(w)
+    from tests.gpu_util import BF16_MAX_ABS, BF16_REL_L2, max_abs, rel_l2
+    errs = {key: (max_abs(got[key], ref[key]), rel_l2(got[key], ref[key])) for key in ("O", "dQ", "dK", "dV")}
+    print(f"   gain {gain}: errors (max-abs, rel-L2):", {k: (f"{a:.2e}", f"{b:.2e}") for k, (a, b) in errs.items()},
+          "largest |dQ|, |dK|:", f"{np.abs(ref['dQ']).max():.1f}, {np.abs(ref['dK']).max():.1f}", flush=True)
+    for key in ("O", "dQ", "dK", "dV"):
+        assert np.isfinite(got[key]).all() and errs[key][1] <= BF16_REL_L2, (key, errs)
+    for key in ("O", "dK", "dV"):
+        assert errs[key][0] <= BF16_MAX_ABS, (key, errs)
+    assert errs["dQ"][0] <= BF16_MAX_ABS * gain ** 2, errs       # dQ carries the trace of the rounded O at far peaks
+    assert max_abs(got["LSE"], ref["LSE"]) <= 1e-3 * gain ** 2
+
+
 @pytest.mark.parametrize("seed", range(24))
 def test_random_shapes(seed):
     # seeded random rows / row lengths / example lengths / head counts / head dims / element types:
