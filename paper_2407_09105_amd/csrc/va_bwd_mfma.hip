@@ -9,7 +9,8 @@
 // Two kernels, no atomics, bitwise reproducible:
 //   dq_mfma_kernel   : workgroup = (128-query tile, query head); streams K/V blocks of 64 rows.
 //                      Lane owns a query row: S^T = K Q^T, dP^T = V dO^T, dQ^T += K^T dS^T.  It also
-//                      forms D for its rows and stores it for the other kernel, so it runs first.
+//                      forms D for its rows (dO . O, then made exact by the row sums of dS) and stores
+//                      it for the other kernel, so it runs first.
 //   dkdv_mfma_kernel : workgroup = (128- or 64-key tile, KV head); streams Q/dO blocks of 64 rows of
 //                      every query head of the group.  Lane owns a key row: S = Q K^T, dP = dO V^T,
 //                      dV^T += dO^T P, dK^T += Q^T dS; the dV and the dK halves run on different waves.
