@@ -166,7 +166,9 @@ va_status va_varlen_attn_fwd(const void *Q, const void *K, const void *V, void *
  *     dQ_i = scale * sum_j dS_ij k_j
  *     dK_j = scale * sum_{i >= j} dS_ij q_i,   dV_j = sum_{i >= j} P_ij dO_i
  * with dK, dV also summed over the Hq / Hkv query heads of a KV head.  Same mask, same
- * skipped tiles.  Results are deterministic (no atomics).
+ * skipped tiles.  Results are deterministic (no atomics).  The 16-bit kernels accumulate in fp32;
+ * they take D from the row sums of dS (which removes the rounding of the stored O) and carry the
+ * large entries of P and dS through the matrix units in two 16-bit parts.
  *   grad_dt   : element type of dQ, dK, dV: VA_F32, or the 16-bit type of the inputs (VA_BF16 also
  *               with fp32 inputs); other pairs: VA_ERR_UNSUPPORTED.
  *   workspace : >= va_attn_workspace_bytes(..., 1) bytes (holds D, [Hq, N] float).
