@@ -99,9 +99,9 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   // Prologue.  The tile's own Q, dO and O rows come in through LDS as whole-row block copies, into
   // the memory of the K/V stages, which is idle until the loop starts (loading the per-lane
   // fragments straight from HBM -- 32 rows x 32 B per instruction -- took 8 us per workgroup):
-  //   round 1: Q -> first half of the stage memory, dO -> second half; scalars (example bounds, LSE)
-  //   round 2: O -> second half, first K/V block -> first half (= stage 0 of the loop)
-  // All loads of a round are requested before any is consumed.
+  //   batch 1: Q -> first half of the stage memory, dO -> second half; scalars (example bounds, LSE)
+  //   batch 2: O -> second half, first K/V block -> first half (= stage 0 of the loop)
+  // All loads of a batch are requested before any is consumed.
   const int iw0 = t0 + wave * 32;
   const int iw1 = min(iw0 + 31, t_last);
   const bool wave_ok = iw0 <= t_last;
@@ -175,7 +175,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 
   x8 qf[kKs], gf[kKs];  // Q and dO rows of this lane: B operands
   wait_all_loads();
-  __syncthreads();  // round 1 has landed
+  __syncthreads();  // batch 1 has landed
 #pragma unroll
   for (int ks = 0; ks < kKs; ++ks) {
     qf[ks] = swz_read_row<E>(K0 + (ks >> 3) * kTileSub, row_lane, ks & 7, wave * 32);
@@ -186,7 +186,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   copy_block(K0, V0, jb_lo);
   const float lse2 = lse_v * kLog2e;
   wait_all_loads();
-  __syncthreads();  // round 2 has landed
+  __syncthreads();  // batch 2 has landed
   // D = dO . O of this lane's query row, computed here (each lane of a pair holds half of the row)
   // and left in `delta` for the dK/dV kernel, which runs after this one
   float dl = 0.f;
