@@ -40,15 +40,19 @@ constexpr float kSplitS = 1.0f;
 // Waves holding queries with fewer keys than this correct their dQ for the rounding of O in
 // D = dO . O (see dq_mfma_kernel).
 constexpr int kNearCtx = 32;
+constexpr int kAheadKv = 3;  // dK/dV kernel: the same for the one product S (or dP) of a wave
+constexpr int kAhead = 2;  // dQ kernel: k-steps by which the LDS fragment reads of S and dP run ahead of their matrix instructions
 
 template <class E> struct needs_split { static constexpr bool value = false; };
 template <> struct needs_split<Bf16> { static constexpr bool value = true; };
 
-// max |x[v]| over a lane's 16 accumulator values
+// max |x[v]| over a lane's 16 accumulator values.  x must come from vector arithmetic (not straight from
+// a matrix instruction: the compiler does not see a hazard through the asm).  Written as three-operand
+// maxima with magnitude modifiers, 8 instructions; from fmaxf(fabsf()) the compiler makes 27.
 __device__ __forceinline__ float abs_max16(const f32x16 &x) {
-  float m = fmaxf(fabsf(x[0]), fabsf(x[1]));
+  float m = 0.f;
 #pragma unroll
-  for (int v = 2; v < 16; v += 2) m = fmaxf(m, fmaxf(fabsf(x[v]), fabsf(x[v + 1])));
+  for (int v = 0; v < 16; v += 2) asm("v_max3_f32 %0, |%1|, |%2|, %3" : "=v"(m) : "v"(x[v]), "v"(x[v + 1]), "v"(m));
   return m;
 }
 // Rounding residuals x[v0..v0+7] - float(hi[0..7]) as a second operand.
@@ -214,20 +218,40 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
         f32x16 s, dp;  // dP accumulates onto -D of this lane's query row
 #pragma unroll
         for (int v = 0; v < 16; ++v) { s[v] = 0.f; dp[v] = -dl; }
+        // Fragment reads run kAhead k-steps ahead of the matrix instructions that use them, in this order
+        // (the scheduling barriers keep it): left alone the compiler requests each pair of fragments right
+        // before the pair of matrix instructions that uses it, and the wave waits out the LDS latency 8 times.
+        x8 kf[kAhead], vf[kAhead];
+#pragma unroll
+        for (int ks = 0; ks < kAhead; ++ks) {
+          kf[ks] = swz_read_row<E>(Kb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32);
+          vf[ks] = swz_read_row<E>(Vb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32);
+        }
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int ks = 0; ks < kKs; ++ks) {
-          s = mfma32(swz_read_row<E>(Kb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32), qf[ks], s);     // S^T  = K Q^T
-          dp = mfma32(swz_read_row<E>(Vb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32), gf[ks], dp);   // dP^T - D = V dO^T - D
+          s = mfma32(kf[ks % kAhead], qf[ks], s);     // S^T  = K Q^T
+          dp = mfma32(vf[ks % kAhead], gf[ks], dp);   // dP^T - D = V dO^T - D
+          if (ks + kAhead < kKs) {
+            const int kn = ks + kAhead;
+            kf[ks % kAhead] = swz_read_row<E>(Kb + (kn >> 3) * kBlk, row_lane, kn & 7, sb * 32);
+            vf[ks % kAhead] = swz_read_row<E>(Vb + (kn >> 3) * kBlk, row_lane, kn & 7, sb * 32);
+          }
+          __builtin_amdgcn_sched_barrier(0);
         }
         const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          float p = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -lse2));
-          if (!interior) {
+        for (int v = 0; v < 16; ++v) s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -lse2));  // P^T
+        if (!interior) {  // one wave-uniform branch around all 16 tests (inside the loop above it stays 16 branches)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) {
             const int j = jl + acc_row(v, half);
-            if (j < ss_i || j > i_abs) p = 0.f;
+            if (j < ss_i || j > i_abs) s[v] = 0.f;
           }
-          s[v] = p * dp[v];  // dS~^T = P (dP - D~)
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          s[v] *= dp[v];  // dS~^T = P (dP - D~)
           csum += s[v];
         }
         // large score gradients are carried in two bf16 parts: a second pass with the residuals
@@ -371,14 +395,21 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   constexpr int kStagingElems = kWaves * kStageFloatsPerWave * 2;
   constexpr int kStagesElems = kStagingElems > 2 * kStage ? kStagingElems : 2 * kStage;
   static_assert(!kKvInStage || 2 * kHf * kKvSub <= kStage, "the tile's K and V rows must fit in one stage");
-  __shared__ __attribute__((aligned(16))) uint16_t stages[kStagesElems];
-  // P hand-over: [key group][parity 2][part 2][lane 64] x 16 B
-  __shared__ __attribute__((aligned(16))) u32x4 exch[kKg * 2 * 2 * 64];
-  // the tile's own K rows and V rows (swizzled like the streamed blocks), only used in the prologue:
-  // each wave takes its 32-row operand from here.  Going through LDS lets the rows arrive as whole
-  // 1 KB transfers; loading the per-lane fragments straight from HBM (32 rows x 32 B per
-  // instruction) took 3 us per workgroup.
-  __shared__ __attribute__((aligned(16))) uint16_t kv_own[kKvInStage ? 8 : 2 * kKvSub];
+  // One LDS object for everything (with several, the compiler makes every LDS read after a block copy
+  // wait until the copy has landed: it can tell copy destinations from read addresses by offset inside
+  // one object only):
+  //   stages: as above
+  //   exch:   P hand-over, [key group][parity 2][part 2][lane 64] x 16 B
+  //   kv_own: the tile's own K rows and V rows (swizzled like the streamed blocks), only used in the
+  //           prologue: each wave takes its 32-row operand from here.  Going through LDS lets the rows
+  //           arrive as whole 1 KB transfers; loading the per-lane fragments straight from HBM (32 rows x
+  //           32 B per instruction) took 3 us per workgroup.
+  constexpr int kExchElems = kKg * 2 * 2 * 64 * 8;
+  constexpr int kKvOwnElems = kKvInStage ? 0 : 2 * kKvSub;
+  __shared__ __attribute__((aligned(16))) uint16_t lds_all[kStagesElems + kExchElems + kKvOwnElems];
+  uint16_t *const stages = lds_all;
+  u32x4 *const exch = (u32x4 *)(lds_all + kStagesElems);
+  uint16_t *const kv_own = lds_all + kStagesElems + kExchElems;
 
   const int lane = threadIdx.x & 63, wave = uniform(threadIdx.x >> 6);
   const int kg = wave % kKg;
@@ -514,11 +545,20 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
 #pragma unroll
       for (int b = 0; b < 4; ++b) x[q4 * 4 + b] = c[b];
     }
-    x8 ax[kKs];
+    // fragment reads run kAheadKv k-steps ahead of their matrix instructions (see kAhead)
+    x8 ax[kAheadKv];
 #pragma unroll
-    for (int ks = 0; ks < kKs; ++ks) ax[ks] = swz_read_row<E>(Xs + (ks >> 3) * kBlk, row_lane, ks & 7, row0);
+    for (int ks = 0; ks < kAheadKv; ++ks) ax[ks] = swz_read_row<E>(Xs + (ks >> 3) * kBlk, row_lane, ks & 7, row0);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < kKs; ++ks) x = mfma32(ax[ks], rf[ks], x);  // S - LSE / scale, or dP - D
+    for (int ks = 0; ks < kKs; ++ks) {
+      x = mfma32(ax[ks % kAheadKv], rf[ks], x);  // S - LSE / scale, or dP - D
+      if (ks + kAheadKv < kKs) {
+        const int kn = ks + kAheadKv;
+        ax[ks % kAheadKv] = swz_read_row<E>(Xs + (kn >> 3) * kBlk, row_lane, kn & 7, row0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
   };
   // `split` (wave-uniform): x holds entries large enough for their bf16 rounding to matter; their
   // residuals go through the matrix pipe as a second operand (see kSplitP / kSplitS)
@@ -560,7 +600,10 @@ dkdv_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q
   auto k_finish = [&](f32x16 &x, const x8 (&ty)[2][kCb], int pr) {  // dS = P (dP - D); dK
     const f16x8 p0 = as_x8<F16>(ex[pr * 128]), p1 = as_x8<F16>(ex[pr * 128 + 64]);
 #pragma unroll
-    for (int e = 0; e < 8; ++e) { x[e] *= (float)p0[e]; x[8 + e] *= (float)p1[e]; }
+    for (int e = 0; e < 8; ++e) {  // written as fma(p, x, +0): one mixed-precision instruction instead of convert + multiply
+      x[e] = __builtin_fmaf((float)p0[e], x[e], 0.f);
+      x[8 + e] = __builtin_fmaf((float)p1[e], x[8 + e], 0.f);
+    }
     second_product(x, ty, needs_split<E>::value && __any(abs_max16(x) > kSplitS));
   };
   bool more = false;
