@@ -239,6 +239,12 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
           }
           __builtin_amdgcn_sched_barrier(0);
         }
+        // K^T fragments of the sub-block's first 16 keys: requested here, in the registers the row
+        // fragments have just left, so that they arrive during the vector work below
+        x8 kt0[kCb], kt1[kCb];
+#pragma unroll
+        for (int cb = 0; cb < kCb; ++cb) kt0[cb] = swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32);
+        __builtin_amdgcn_sched_barrier(0);
         const bool interior = wave_full && jl >= ss_max && jl + 31 <= iw0;
 #pragma unroll
         for (int v = 0; v < 16; ++v) s[v] = __builtin_amdgcn_exp2f(fmaf(s[v], scale_log2, -lse2));  // P^T
@@ -255,21 +261,17 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
           csum += s[v];
         }
         // large score gradients are carried in two bf16 parts: a second pass with the residuals
-        // (wave-uniform choice; rare on long examples, so the K^T fragments are simply read again)
+        // (wave-uniform choice; rare on long examples)
         const bool split = needs_split<E>::value && __any(abs_max16(s) > kSplitS);
         const x8 df0 = pack_x8<E>(s, 0), df1 = pack_x8<E>(s, 8);
-        x8 dr0 = df0, dr1 = df1;
-        if (split) {
-          dr0 = pack_residual_x8<E>(s, 0, df0);
-          dr1 = pack_residual_x8<E>(s, 8, df1);
-        }
 #pragma unroll
-        for (int cb = 0; cb < kCb; ++cb)  // dQ^T += K^T dS^T
-          acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32), df0, acc[cb]);
+        for (int cb = 0; cb < kCb; ++cb) kt1[cb] = swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + 16);
 #pragma unroll
-        for (int cb = 0; cb < kCb; ++cb)
-          acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + 16), df1, acc[cb]);
-        if (split) {
+        for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(kt0[cb], df0, acc[cb]);  // dQ^T += K^T dS^T
+#pragma unroll
+        for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(kt1[cb], df1, acc[cb]);
+        if (split) {  // the K^T fragments are simply read again
+          const x8 dr0 = pack_residual_x8<E>(s, 0, df0), dr1 = pack_residual_x8<E>(s, 8, df1);
 #pragma unroll
           for (int cb = 0; cb < kCb; ++cb)
             acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32), dr0, acc[cb]);
