@@ -40,8 +40,11 @@ constexpr float kSplitS = 1.0f;
 // Waves holding queries with fewer keys than this correct their dQ for the rounding of O in
 // D = dO . O (see dq_mfma_kernel).
 constexpr int kNearCtx = 32;
-constexpr int kAheadKv = 3;  // dK/dV kernel: the same for the one product S (or dP) of a wave
-constexpr int kAhead = 2;  // dQ kernel: k-steps by which the LDS fragment reads of S and dP run ahead of their matrix instructions
+// k-steps by which the LDS fragment reads of S and dP run ahead of the matrix instructions that use
+// them: in the dQ kernel (two products interleaved) and in the dK/dV kernel (one product per wave).
+// Depths 2 to 4 measure the same; the rings occupy registers that the next phase's fragments reuse.
+constexpr int kAhead = 2;
+constexpr int kAheadKv = 3;
 
 template <class E> struct needs_split { static constexpr bool value = false; };
 template <> struct needs_split<Bf16> { static constexpr bool value = true; };
@@ -342,7 +345,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
 // dK/dV with the two gradients on different waves.  Workgroup = 8 waves = (128-key tile, KV head);
 // waves 0..3 ("V side") and 4..7 ("K side") each own 32 keys, wave w and w + 4 the same ones, and
 // share a SIMD.  Per 32-query sub-block:
-//   V side: S = Q K^T (on -LSE / scale), P = exp2, mask; leaves P (bf16) in LDS for its partner;
+//   V side: S = Q K^T (on -LSE / scale), P = exp2, mask; leaves P (fp16) in LDS for its partner;
 //           dV^T += dO^T P.
 //   K side: dP = dO V^T (on -D); one sub-block later, with that P: dS = P * dP; dK^T += Q^T dS.
 // Each wave holds one accumulator tile and one operand tile (about 200 registers), so two waves fit
