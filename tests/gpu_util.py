@@ -33,9 +33,16 @@ def max_abs(x, ref) -> float:
     return float(np.abs(x.astype(np.float64) - ref).max()) if x.size else 0.0
 
 
-def run_gpu(w, grad_dtype=None, scale=0.0, pos_dtype=torch.int64, nan_fill=False):
+def bench_hint(w):
+    """The example-length hint bench.py passes for this workload (same rule: mean length against 1024)."""
+    n = int(oracle.pack(w.position_ids)["cu_seqlens"].size) - 1
+    return binding.HINT_LONG_EXAMPLES if w.position_ids.size >= 1024 * n else binding.HINT_SHORT_EXAMPLES
+
+
+def run_gpu(w, grad_dtype=None, scale=0.0, pos_dtype=torch.int64, nan_fill=False, hint=0):
     """Full path on the GPU: pack -> fwd -> bwd.  Returns host numpy arrays (float64).
-    nan_fill: the outputs start as NaN, so that an element no workgroup writes shows."""
+    nan_fill: the outputs start as NaN, so that an element no workgroup writes shows.
+    hint: an example-length hint for the backward (0: the device chooses the dK/dV shape)."""
     dt = w.cfg.dtype
     pos = torch.from_numpy(w.position_ids).to(DEV).to(pos_dtype)
     q, k, v, do = (to_dev(a, dt) for a in (w.q, w.k, w.v, w.do))
@@ -47,8 +54,9 @@ def run_gpu(w, grad_dtype=None, scale=0.0, pos_dtype=torch.int64, nan_fill=False
         pre = dict(out=nan(q.shape, q.dtype), lse=nan((q.shape[1], q.shape[0]), torch.float32),
                    dq=nan(q.shape, gdt), dk=nan(k.shape, gdt), dv=nan(v.shape, gdt))
     o, lse = binding.varlen_attn_fwd(q, k, v, seg, scale, out=pre.get("out"), lse=pre.get("lse"))
+    stages = (binding.STAGE_D | binding.STAGE_DQ | binding.STAGE_DKDV | hint) if hint else None
     dq, dk, dv = binding.varlen_attn_bwd(do, q, k, v, o, lse, seg, scale, grad_dtype=grad_dtype,
-                                         dq=pre.get("dq"), dk=pre.get("dk"), dv=pre.get("dv"))
+                                         dq=pre.get("dq"), dk=pre.get("dk"), dv=pre.get("dv"), stages=stages)
     torch.cuda.synchronize()
     f = lambda t: t.float().cpu().numpy().astype(np.float64)
     return {"seg": seg.host(), "O": f(o), "LSE": f(lse), "dQ": f(dq), "dK": f(dk), "dV": f(dv)}
