@@ -94,6 +94,9 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
     for (int v = 0; v < 16; ++v) o_acc[cb][v] = 0.f;
   float m_ref = -INFINITY;  // reference maximum the stored probabilities are relative to (raw scores)
   float l_run = 0.f;        // this lane's share of the running row sum, relative to m_ref
+  float m_thr = -INFINITY;  // m_ref + kLazyLog2 / scale_log2: a block maximum above it moves m_ref
+  float mneg = 0.f;         // -m_ref * scale_log2; 0 while m_ref = -inf (nothing unmasked yet), so that exp2(-inf - 0) = 0
+  const float lazy_raw = kLazyLog2 / scale_log2;
 
   // K/V block loads: buffer descriptors based at the workgroup's first key row
   const size_t row_bytes = (size_t)hkv * d * 2;
@@ -154,7 +157,7 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
 #pragma unroll
         for (int v = 2; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[v]), s[v + 1]);
         mx = pair_max(mx);
-        if (__any((mx - m_ref) * scale_log2 > kLazyLog2)) {  // rare after the first block
+        if (__any(mx > m_thr)) {  // rare after the first block
           const float m_new = fmaxf(m_ref, mx);
           const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f((m_ref - m_new) * scale_log2);
           l_run *= alpha;
@@ -163,9 +166,9 @@ fwd_mfma_kernel(const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K,
 #pragma unroll
             for (int v = 0; v < 16; ++v) o_acc[cb][v] *= alpha;
           m_ref = m_new;
+          m_thr = m_new + lazy_raw;
+          mneg = (m_new == -INFINITY) ? 0.f : -m_new * scale_log2;
         }
-        // rows with nothing unmasked so far have m_ref = -inf: use 0 so that exp2(-inf - 0) = 0
-        const float mneg = (m_ref == -INFINITY) ? 0.f : -m_ref * scale_log2;
         float psum = 0.f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
