@@ -148,7 +148,12 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   const int ss_i_v = seg_start[i_ld];
   const float lse_v = LSE[(size_t)h * N + i_ld];
 
-  const int jb_lo = uniform(ss_t0_v) / kBS, jb_hi = t_last / kBS;
+  // Key blocks are counted from the packed row's first token (block jb = tokens jbase + 64 jb ...):
+  // a tile's own rows are then exactly its last two blocks whatever T, which the short-context
+  // correction after the loop relies on (with blocks counted from token 0 a tile of a row that does
+  // not start on a multiple of 64 straddles three).
+  const int jbase = (r * T) % kBS;
+  const int jb_lo = (uniform(ss_t0_v) - jbase) / kBS, jb_hi = (t_last - jbase) / kBS;  // jb_hi - 1, jb_hi: the tile's own rows
   const int ss_min = uniform(ss_min_v), ss_max = uniform(ss_max_v);
   const int ss_i = row_ok ? ss_i_v : 0x7fffffff;
   f32x16 acc[kCb];
@@ -158,7 +163,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
     for (int v = 0; v < 16; ++v) acc[cb][v] = 0.f;
 
   const size_t row_bytes = (size_t)hkv * d * 2;
-  const size_t base_off = (size_t)jb_lo * kBS * row_bytes;
+  const size_t base_off = ((size_t)jb_lo * kBS + jbase) * row_bytes;
   const size_t total = (size_t)N * row_bytes;
   const buffer_t kbuf = make_buffer((const char *)K + base_off, total - base_off);
   const buffer_t vbuf = make_buffer((const char *)V + base_off, total - base_off);
@@ -177,6 +182,23 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
         const uint32_t o = dma_ok[hf] ? off + p * p_bytes + hf * 256 : kPastEnd;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(Kd + hf * kBlk + (4 * p + wave) * 512), 16, o, 0, 0, 0);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(vbuf, (lds_void)(Vd + hf * kBlk + (4 * p + wave) * 512), 16, o, 0, 0, 0);
+      }
+  };
+
+  // The example of the tile's first row began fewer than kNearCtx tokens before the tile (workgroup-
+  // uniform): the short-context correction of the first wave then needs the K rows t0 - 32 .. t0 - 1,
+  // the second half of block jb_hi - 2, which has left the stages by the end of the loop.  They are
+  // copied once more during the last iteration, into the V half of the other stage (dead by then).
+  const int ss_t0 = uniform(ss_t0_v);
+  const bool need_prev = ss_t0 < t0 && t0 - ss_t0 < kNearCtx && jb_hi - 2 >= jb_lo;
+  auto copy_prev_half = [&](uint16_t *dst) {
+    const uint32_t off = dma_off + (uint32_t)(jb_hi - 2 - jb_lo) * blk_bytes;
+#pragma unroll
+    for (int hf = 0; hf < kHf; ++hf)
+#pragma unroll
+      for (int p = 2; p < 4; ++p) {
+        const uint32_t o = dma_ok[hf] ? off + p * p_bytes + hf * 256 : kPastEnd;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(dst + hf * kBlk + (4 * p + wave) * 512), 16, o, 0, 0, 0);
       }
   };
 
@@ -212,7 +234,8 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   auto iteration = [&](int jb, const uint16_t *__restrict__ Kb, const uint16_t *__restrict__ Vb,
                        uint16_t *__restrict__ Kn, uint16_t *__restrict__ Vn) {
     if (jb < jb_hi) copy_block(Kn, Vn, jb + 1);  // workgroup-uniform
-    const int j0 = jb * kBS;
+    else if (need_prev) copy_prev_half(Vn);
+    const int j0 = jbase + jb * kBS;
     if (wave_ok && j0 <= iw1 && j0 + kBS - 1 >= ss_min) {  // wave-uniform
 #pragma unroll
       for (int sb = 0; sb < 2; ++sb) {
@@ -301,38 +324,45 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   // probabilities are large, i.e. for queries with a short context (it falls off as 1 / context^2).
   // Waves that hold queries with fewer than kNearCtx keys recompute P on the key sub-blocks from
   // kNearCtx before their first row on and add K^T (-c P)^T - on the last two key blocks only, which
-  // are still in the stage memory (nothing was copied after them): no copy, no extra barrier.  A
-  // short-context query at the very start of a tile whose example began in an earlier block keeps
-  // the part of the correction that belongs to those earlier keys (its dQ then carries the 1e-2-size
-  // trace of the rounded O that every query carried before).
+  // are still in the stage memory (nothing was copied after them): no copy, no extra barrier - and,
+  // where the example of the tile's first row began shortly before the tile, on the 32 keys before the
+  // tile (copy_prev_half above: one 8 KB copy under the last iteration and one barrier).
+  if (need_prev) {  // workgroup-uniform: the extra rows were requested an iteration ago
+    wait_all_loads();
+    __syncthreads();
+  }
   if (wave_ok && ss_max > iw0 - kNearCtx) {  // wave-uniform
     const int j_first = max(ss_min, iw0 - kNearCtx);
+    auto near_sub = [&](const uint16_t *Kb, int row0, int jl) {  // keys jl .. jl + 31 = rows row0 .. of the block at Kb
+      f32x16 sc;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < kKs; ++ks)
+        sc = mfma32(swz_read_row<E>(Kb + (ks >> 3) * kBlk, row_lane, ks & 7, row0), qf[ks], sc);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int j = jl + acc_row(v, half);
+        const float p = __builtin_amdgcn_exp2f(fmaf(sc[v], scale_log2, -lse2));
+        sc[v] = (j < ss_i || j > i_abs) ? 0.f : -c_row * p;
+      }
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2) {
+        const x8 cf = pack_x8<E>(sc, 8 * s2);
+#pragma unroll
+        for (int cb = 0; cb < kCb; ++cb)
+          acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, row0 + s2 * 16), cf, acc[cb]);
+      }
+    };
+    if (need_prev && wave == 0) near_sub(((jb_hi - jb_lo) & 1) ? V0 : V1, 32, t0 - 32);
 #pragma unroll 1
     for (int jb = max(jb_lo, jb_hi - 1); jb <= jb_hi; ++jb) {
       const uint16_t *Kb = ((jb - jb_lo) & 1) ? K1 : K0;
 #pragma unroll 1
       for (int sb = 0; sb < 2; ++sb) {
-        const int jl = jb * kBS + sb * 32;
+        const int jl = jbase + jb * kBS + sb * 32;
         if (jl > iw1 || jl + 31 < j_first) continue;  // wave-uniform
-        f32x16 sc;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) sc[v] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < kKs; ++ks)
-          sc = mfma32(swz_read_row<E>(Kb + (ks >> 3) * kBlk, row_lane, ks & 7, sb * 32), qf[ks], sc);
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int j = jl + acc_row(v, half);
-          const float p = __builtin_amdgcn_exp2f(fmaf(sc[v], scale_log2, -lse2));
-          sc[v] = (j < ss_i || j > i_abs) ? 0.f : -c_row * p;
-        }
-#pragma unroll
-        for (int s2 = 0; s2 < 2; ++s2) {
-          const x8 cf = pack_x8<E>(sc, 8 * s2);
-#pragma unroll
-          for (int cb = 0; cb < kCb; ++cb)
-            acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, sb * 32 + s2 * 16), cf, acc[cb]);
-        }
+        near_sub(Kb, sb * 32, jl);
       }
     }
   }

@@ -49,3 +49,28 @@ def test_sweep_seed_meets_the_stated_bar(seed):
     ref = run_oracle(w)
     assert_seg_equal(got["seg"], ref["seg"])
     assert_close(got, ref, w.cfg.dtype)
+
+
+# Short-context queries (the first few tokens of an example) are where the rounding of the stored O
+# shows most in dQ: D = dO . O is off by 2^-9 |dO . O| and the few probabilities are large.  The dQ kernel
+# corrects them after its loop from key blocks that are still in LDS; two layouts had escaped it and sat
+# at 0.9e-2 .. 1.6e-2 (inside the stated 2e-2, far above everything else in the tensor):
+#   - packed rows that do not start on a multiple of 64 tokens (T % 64 != 0): key blocks were counted
+#     from token 0, so a tile's own rows straddled three blocks and the first was gone by then;
+#   - a tile whose first row belongs to an example that began a few tokens before the tile.
+# The bound below is what the corrected rows reach; the far-peaked rows of head_dim 8 in the same sweep
+# (no correction: see the design notes) are not in these cases.
+SHORT_CONTEXT = [3119, 3093, 3055, 3128, 3142]
+
+
+@pytest.mark.parametrize("seed", SHORT_CONTEXT)
+def test_short_context_rows_are_corrected(seed):
+    w = sweep_case(seed)
+    print(f"case: sweep seed {seed} R={w.cfg.rows} T={w.cfg.tokens_per_row} hq={w.cfg.hq} hkv={w.cfg.hkv} "
+          f"d={w.cfg.d} {w.cfg.dtype}", flush=True)
+    got = run_gpu(w, grad_dtype=torch.float32, nan_fill=True)
+    ref = run_oracle(w)
+    assert_close(got, ref, w.cfg.dtype)
+    err = float(np.abs(got["dQ"] - ref["dQ"]).max())
+    print(f"   dQ max-abs {err:.2e}", flush=True)
+    assert err <= 6e-3
