@@ -39,7 +39,7 @@ constexpr float kSplitP = 0.125f;
 constexpr float kSplitS = 1.0f;
 // Waves holding queries with fewer keys than this correct their dQ for the rounding of O in
 // D = dO . O (see dq_mfma_kernel).
-constexpr int kNearCtx = 32;
+constexpr int kNearCtx = 64;
 // k-steps by which the LDS fragment reads of S and dP run ahead of the matrix instructions that use
 // them: in the dQ kernel (two products interleaved) and in the dK/dV kernel (one product per wave).
 // Depths 2 to 4 measure the same; the rings occupy registers that the next phase's fragments reuse.
@@ -186,17 +186,20 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   };
 
   // The example of the tile's first row began fewer than kNearCtx tokens before the tile (workgroup-
-  // uniform): the short-context correction of the first wave then needs the K rows t0 - 32 .. t0 - 1,
-  // the second half of block jb_hi - 2, which has left the stages by the end of the loop.  They are
-  // copied once more during the last iteration, into the V half of the other stage (dead by then).
+  // uniform): the short-context correction of the first waves then needs the kNearCtx K rows before the
+  // tile, the end of block jb_prev = jb_hi - 2, which has left the stages by the end of the loop.  They
+  // are copied once more during the last iteration, into the V half of the other stage (dead by then).
+  // (A tile of at most 64 rows has jb_prev = jb_hi - 1, still in its stage: nothing to copy.)
+  static_assert(kNearCtx == 32 || kNearCtx == 64, "the rows kept for the correction are part of one 64-row block");
   const int ss_t0 = uniform(ss_t0_v);
-  const bool need_prev = ss_t0 < t0 && t0 - ss_t0 < kNearCtx && jb_hi - 2 >= jb_lo;
-  auto copy_prev_half = [&](uint16_t *dst) {
-    const uint32_t off = dma_off + (uint32_t)(jb_hi - 2 - jb_lo) * blk_bytes;
+  const int jb_prev = (t0 - jbase) / kBS - 1;
+  const bool need_prev = ss_t0 < t0 && t0 - ss_t0 < kNearCtx && jb_prev == jb_hi - 2 && jb_prev >= jb_lo;
+  auto copy_prev_rows = [&](uint16_t *dst) {
+    const uint32_t off = dma_off + (uint32_t)(jb_prev - jb_lo) * blk_bytes;
 #pragma unroll
     for (int hf = 0; hf < kHf; ++hf)
 #pragma unroll
-      for (int p = 2; p < 4; ++p) {
+      for (int p = (kBS - kNearCtx) / 16; p < 4; ++p) {
         const uint32_t o = dma_ok[hf] ? off + p * p_bytes + hf * 256 : kPastEnd;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(kbuf, (lds_void)(dst + hf * kBlk + (4 * p + wave) * 512), 16, o, 0, 0, 0);
       }
@@ -234,7 +237,7 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   auto iteration = [&](int jb, const uint16_t *__restrict__ Kb, const uint16_t *__restrict__ Vb,
                        uint16_t *__restrict__ Kn, uint16_t *__restrict__ Vn) {
     if (jb < jb_hi) copy_block(Kn, Vn, jb + 1);  // workgroup-uniform
-    else if (need_prev) copy_prev_half(Vn);
+    else if (need_prev) copy_prev_rows(Vn);
     const int j0 = jbase + jb * kBS;
     if (wave_ok && j0 <= iw1 && j0 + kBS - 1 >= ss_min) {  // wave-uniform
 #pragma unroll
@@ -325,8 +328,10 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   // Waves that hold queries with fewer than kNearCtx keys recompute P on the key sub-blocks from
   // kNearCtx before their first row on and add K^T (-c P)^T - on the last two key blocks only, which
   // are still in the stage memory (nothing was copied after them): no copy, no extra barrier - and,
-  // where the example of the tile's first row began shortly before the tile, on the 32 keys before the
-  // tile (copy_prev_half above: one 8 KB copy under the last iteration and one barrier).
+  // where the example of the tile's first row began shortly before the tile, on the kNearCtx keys before
+  // the tile (copy_prev_rows above: one copy under the last iteration and one barrier).  With 64 instead of
+  // 32 the rows whose softmax peaks a few dozen keys back are covered too (dQ of a batch of 8..128-token
+  // examples: 1.1e-2 -> 3.7e-3 max-abs) for 7 % of this kernel's time on such a batch, under 2 % elsewhere.
   if (need_prev) {  // workgroup-uniform: the extra rows were requested an iteration ago
     wait_all_loads();
     __syncthreads();
@@ -354,7 +359,14 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
           acc[cb] = mfma32(swz_read_tr<E>(Kb + (cb >> 2) * kBlk, tr_lane, cb & 3, row0 + s2 * 16), cf, acc[cb]);
       }
     };
-    if (need_prev && wave == 0) near_sub(((jb_hi - jb_lo) & 1) ? V0 : V1, 32, t0 - 32);
+    if (need_prev && iw0 - kNearCtx < t0) {  // wave-uniform: this wave's keys begin before the tile
+      const uint16_t *Kp = ((jb_hi - jb_lo) & 1) ? V0 : V1;
+#pragma unroll 1
+      for (int sb = (kBS - kNearCtx) / 32; sb < 2; ++sb) {
+        const int jl = t0 - kBS + sb * 32;
+        if (jl + 31 >= j_first) near_sub(Kp, sb * 32, jl);
+      }
+    }
 #pragma unroll 1
     for (int jb = max(jb_lo, jb_hi - 1); jb <= jb_hi; ++jb) {
       const uint16_t *Kb = ((jb - jb_lo) & 1) ? K1 : K0;
