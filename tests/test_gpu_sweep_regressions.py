@@ -74,3 +74,16 @@ def test_short_context_rows_are_corrected(seed):
     err = float(np.abs(got["dQ"] - ref["dQ"]).max())
     print(f"   dQ max-abs {err:.2e}", flush=True)
     assert err <= 6e-3
+
+
+@pytest.mark.parametrize("rows", [[[120, 48]], [[60, 70, 38]], [[125, 3, 40]], [[100, 100], [7, 193]], [[190, 66]]])
+def test_short_context_rows_at_ragged_tiles(rows):
+    # the same correction where a packed row ends with a tile of at most 64 rows (the keys before the tile
+    # are then still in their stage) and where rows start off a multiple of 64
+    w = wl.make_custom(rows, 4, 2, 128, "bf16", seed=77)
+    got = run_gpu(w, grad_dtype=torch.float32, nan_fill=True)
+    ref = run_oracle(w)
+    assert_close(got, ref, "bf16")
+    err = float(np.abs(got["dQ"] - ref["dQ"]).max())
+    print(f"   dQ max-abs {err:.2e}", flush=True)
+    assert err <= 6e-3
