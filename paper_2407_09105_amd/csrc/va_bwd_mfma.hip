@@ -191,9 +191,22 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   // are copied once more during the last iteration, into the V half of the other stage (dead by then).
   // (A tile of at most 64 rows has jb_prev = jb_hi - 1, still in its stage: nothing to copy.)
   static_assert(kNearCtx == 32 || kNearCtx == 64, "the rows kept for the correction are part of one 64-row block");
+  // head_dim <= 32 (the smallest instantiation only): the whole correction -c_i sum_j P_ij k_j is kept, in a
+  // second accumulator fed by the K^T fragments the dQ product reads anyway.  The softmax scale 1 / sqrt(d)
+  // is large there, the same error in D weighs 2..4 times more in dQ than at head_dim 128, and the
+  // instantiation has the registers; larger head dims take the correction on the nearest keys only (below).
+  constexpr bool kHasPk = kDh == 64;
+  const bool pk_on = kHasPk && d <= 32;  // workgroup-uniform
+  f32x16 pk[kHasPk ? kCb : 1];
+  if constexpr (kHasPk) {
+#pragma unroll
+    for (int cb = 0; cb < kCb; ++cb)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) pk[cb][v] = 0.f;
+  }
   const int ss_t0 = uniform(ss_t0_v);
   const int jb_prev = (t0 - jbase) / kBS - 1;
-  const bool need_prev = ss_t0 < t0 && t0 - ss_t0 < kNearCtx && jb_prev == jb_hi - 2 && jb_prev >= jb_lo;
+  const bool need_prev = !pk_on && ss_t0 < t0 && t0 - ss_t0 < kNearCtx && jb_prev == jb_hi - 2 && jb_prev >= jb_lo;
   auto copy_prev_rows = [&](uint16_t *dst) {
     const uint32_t off = dma_off + (uint32_t)(jb_prev - jb_lo) * blk_bytes;
 #pragma unroll
@@ -284,6 +297,10 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
             if (j < ss_i || j > i_abs) s[v] = 0.f;
           }
         }
+        x8 pf0, pf1;  // P^T as an operand, where the whole correction is kept
+        if constexpr (kHasPk) {
+          if (pk_on) { pf0 = pack_x8<E>(s, 0); pf1 = pack_x8<E>(s, 8); }
+        }
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
           s[v] *= dp[v];  // dS~^T = P (dP - D~)
@@ -299,6 +316,12 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
         for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(kt0[cb], df0, acc[cb]);  // dQ^T += K^T dS^T
 #pragma unroll
         for (int cb = 0; cb < kCb; ++cb) acc[cb] = mfma32(kt1[cb], df1, acc[cb]);
+        if constexpr (kHasPk) {
+          if (pk_on) {
+#pragma unroll
+            for (int cb = 0; cb < kCb; ++cb) pk[cb] = mfma32(kt1[cb], pf1, mfma32(kt0[cb], pf0, pk[cb]));  // sum_j k_j P_ij
+          }
+        }
         if (split) {  // the K^T fragments are simply read again
           const x8 dr0 = pack_residual_x8<E>(s, 0, df0), dr1 = pack_residual_x8<E>(s, 8, df1);
 #pragma unroll
@@ -332,11 +355,19 @@ dq_mfma_kernel(const uint16_t *__restrict__ dO, const uint16_t *__restrict__ Q,
   // the tile (copy_prev_rows above: one copy under the last iteration and one barrier).  With 64 instead of
   // 32 the rows whose softmax peaks a few dozen keys back are covered too (dQ of a batch of 8..128-token
   // examples: 1.1e-2 -> 3.7e-3 max-abs) for 7 % of this kernel's time on such a batch, under 2 % elsewhere.
+  if constexpr (kHasPk) {
+    if (pk_on) {
+#pragma unroll
+      for (int cb = 0; cb < kCb; ++cb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[cb][v] = fmaf(-c_row, pk[cb][v], acc[cb][v]);
+    }
+  }
   if (need_prev) {  // workgroup-uniform: the extra rows were requested an iteration ago
     wait_all_loads();
     __syncthreads();
   }
-  if (wave_ok && ss_max > iw0 - kNearCtx) {  // wave-uniform
+  if (!pk_on && wave_ok && ss_max > iw0 - kNearCtx) {  // wave-uniform
     const int j_first = max(ss_min, iw0 - kNearCtx);
     auto near_sub = [&](const uint16_t *Kb, int row0, int jl) {  // keys jl .. jl + 31 = rows row0 .. of the block at Kb
       f32x16 sc;

@@ -61,9 +61,12 @@ def test_sweep_seed_meets_the_stated_bar(seed):
 # The bound below is what the corrected rows reach; the far-peaked rows of head_dim 8 in the same sweep
 # (no correction: see the design notes) are not in these cases.
 SHORT_CONTEXT = [3119, 3093, 3055, 3128, 3142]
+# head_dim 8 (softmax scale 0.35: the same error in D weighs four times what it does at head_dim 128) with a
+# probability peak dozens of keys back: 1.0e-2 .. 1.4e-2 before head dims up to 32 kept the whole correction
+SMALL_HEAD_DIM = [3356, 3043, 3395]
 
 
-@pytest.mark.parametrize("seed", SHORT_CONTEXT)
+@pytest.mark.parametrize("seed", SHORT_CONTEXT + SMALL_HEAD_DIM)
 def test_short_context_rows_are_corrected(seed):
     w = sweep_case(seed)
     print(f"case: sweep seed {seed} R={w.cfg.rows} T={w.cfg.tokens_per_row} hq={w.cfg.hq} hkv={w.cfg.hkv} "
