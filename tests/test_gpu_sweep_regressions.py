@@ -58,8 +58,7 @@ def test_sweep_seed_meets_the_stated_bar(seed):
 #   - packed rows that do not start on a multiple of 64 tokens (T % 64 != 0): key blocks were counted
 #     from token 0, so a tile's own rows straddled three blocks and the first was gone by then;
 #   - a tile whose first row belongs to an example that began a few tokens before the tile.
-# The bound below is what the corrected rows reach; the far-peaked rows of head_dim 8 in the same sweep
-# (no correction: see the design notes) are not in these cases.
+# The bound below is what the corrected rows reach.
 SHORT_CONTEXT = [3119, 3093, 3055, 3128, 3142]
 # head_dim 8 (softmax scale 0.35: the same error in D weighs four times what it does at head_dim 128) with a
 # probability peak dozens of keys back: 1.0e-2 .. 1.4e-2 before head dims up to 32 kept the whole correction
